@@ -1,0 +1,270 @@
+"""ctypes marshalling for libfalcon_verify.so.  Function names and semantics are those
+of include/falcon_verify.h; nothing here computes anything."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+STATUS = {0: "FV_OK", -1: "FV_E_BAD_ARG", -2: "FV_E_TREE_ORDER", -3: "FV_E_TREE_DEPTH", -4: "FV_E_TOKEN_RANGE",
+          -5: "FV_E_TREE_TOO_BIG", -6: "FV_E_CACHE_FULL", -7: "FV_E_ROOT_MISMATCH", -8: "FV_E_NO_PREFILL",
+          -9: "FV_E_HIP"}
+PHASES = ("gemm", "fixup", "attn", "other")
+
+
+class FvError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = STATUS.get(status, str(status))
+        if _LIB is not None:
+            msg += ": " + _LIB.fv_status_str(status).decode()
+        super().__init__(f"{where} -> {msg}")
+
+
+class fv_cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab",
+                                         "dtype", "max_seq", "max_tree")] + [("rope_base", C.c_float), ("rms_eps", C.c_float)]
+
+
+class fv_host_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("g_final", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g_attn", "g_mlp")]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libfalcon_verify.so")
+
+
+def load_library():
+    """Load the built library; there is no fallback of any kind."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it first (python -m paper_2412_12639_amd.build, "
+                          "or __graft_entry__.build())")
+    lib = C.CDLL(path)
+    i32p, vp = C.POINTER(C.c_int32), C.c_void_p
+    lib.fv_status_str.restype = C.c_char_p
+    lib.fv_status_str.argtypes = [C.c_int]
+    sigs = {
+        "fv_workspace_bytes": [C.POINTER(fv_cfg), C.POINTER(C.c_size_t)],
+        "fv_validate_tree": [C.POINTER(fv_cfg), i32p, i32p, i32p, C.c_int32, C.c_int32, C.c_int32],
+        "fv_create": [C.POINTER(fv_cfg), vp, C.c_size_t, vp, C.POINTER(vp)],
+        "fv_init_weights": [vp, C.POINTER(fv_host_weights)],
+        "fv_prefill": [vp, i32p, C.c_int32, i32p],
+        "fv_verify_tree": [vp, i32p, i32p, i32p, C.c_int32, i32p, i32p, i32p],
+        "fv_rollback": [vp, C.c_int32, C.c_int32],
+        "fv_get_state": [vp, i32p, i32p],
+        "fv_get_tree_mask": [vp, C.POINTER(C.c_uint64), C.c_int32],
+        "fv_get_logits": [vp, C.POINTER(C.c_float), C.c_int32],
+        "fv_get_argmax": [vp, i32p, C.c_int32],
+        "fv_get_kv_moves": [vp, i32p, i32p, i32p],
+        "fv_read_kv": [vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
+        "fv_debug_read_activation": [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float)],
+        "fv_set_profiling": [vp, C.c_int32],
+        "fv_get_phase_times": [vp, C.POINTER(C.c_float), i32p],
+        "fv_last_step_ms": [vp, C.POINTER(C.c_float)],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    lib.fv_destroy.argtypes = [vp]
+    lib.fv_destroy.restype = None
+    _LIB = lib
+    return lib
+
+
+def make_cfg(shape, max_seq: int, max_tree: int) -> fv_cfg:
+    """`shape` is any object with n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,
+    dtype ("f32" | "bf16"), rope_base, rms_eps."""
+    return fv_cfg(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
+                  shape.vocab, 1 if shape.dtype == "bf16" else 0, max_seq, max_tree, shape.rope_base, shape.rms_eps)
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def validate_tree(shape, max_seq, max_tree, tokens, parent, depth, pending_root, cur_len) -> int:
+    """Host-only tree check (no GPU needed); returns the status code."""
+    lib = load_library()
+    cfg = make_cfg(shape, max_seq, max_tree)
+    t, tp = _i32(tokens)
+    p, pp = _i32(parent)
+    d, dp = _i32(depth)
+    return lib.fv_validate_tree(C.byref(cfg), tp, pp, dp, len(t), int(pending_root), int(cur_len))
+
+
+def workspace_bytes(shape, max_seq, max_tree) -> int:
+    lib = load_library()
+    cfg = make_cfg(shape, max_seq, max_tree)
+    out = C.c_size_t(0)
+    rc = lib.fv_workspace_bytes(C.byref(cfg), C.byref(out))
+    if rc:
+        raise FvError(rc, "fv_workspace_bytes")
+    return out.value
+
+
+class FalconVerifier:
+    """One decoding session on one GPU: owns the torch arena and the fv_ctx."""
+
+    def __init__(self, shape, max_seq: int, max_tree: int, device: str = "cuda:0", stream=None):
+        import torch
+        self.lib = load_library()
+        self.shape, self.max_seq, self.max_tree = shape, max_seq, max_tree
+        self.cfg = make_cfg(shape, max_seq, max_tree)
+        self.bytes = workspace_bytes(shape, max_seq, max_tree)
+        if not torch.cuda.is_available():
+            raise RuntimeError("FalconVerifier needs a GPU: there is no CPU path")
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.arena = torch.empty(self.bytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.arena.data_ptr()
+        self._ptr = (base + 255) // 256 * 256
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        ctx = C.c_void_p()
+        rc = self.lib.fv_create(C.byref(self.cfg), C.c_void_p(self._ptr), C.c_size_t(self.bytes),
+                                C.c_void_p(self.stream.cuda_stream), C.byref(ctx))
+        if rc:
+            raise FvError(rc, "fv_create")
+        self.ctx = ctx
+        self.last_n = 0
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            self.lib.fv_destroy(self.ctx)
+            self.ctx = None
+        self.arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _chk(self, rc, where):
+        if rc:
+            raise FvError(rc, where)
+
+    def init_weights(self, weights: dict):
+        """weights: name -> numpy array as produced for the model shape (matrices float32 or
+        uint16 bf16 bits, gains float32)."""
+        s = self.shape
+        want = np.uint16 if s.dtype == "bf16" else np.float32
+        keep = []
+
+        def ptr(a, dt):
+            a = np.ascontiguousarray(a, dtype=dt)
+            if a.dtype != dt:
+                raise TypeError("weight dtype mismatch")
+            keep.append(a)
+            return a.ctypes.data
+
+        def arr(kind, dt):
+            v = (C.c_void_p * s.n_layers)(*[ptr(weights[f"l{l}.{kind}"], dt) for l in range(s.n_layers)])
+            keep.append(v)
+            return C.cast(v, C.POINTER(C.c_void_p))
+
+        for k, v in weights.items():
+            if v.ndim == 2 and v.dtype != want:
+                raise TypeError(f"{k}: expected {want} for dtype {s.dtype}, got {v.dtype}")
+        hw = fv_host_weights(ptr(weights["embed"], want), ptr(weights["lm_head"], want), ptr(weights["g_final"], np.float32),
+                             arr("wq", want), arr("wk", want), arr("wv", want), arr("wo", want), arr("wg", want),
+                             arr("wu", want), arr("wd", want), arr("g_attn", np.float32), arr("g_mlp", np.float32))
+        self._chk(self.lib.fv_init_weights(self.ctx, C.byref(hw)), "fv_init_weights")
+
+    def prefill(self, tokens) -> int:
+        t, tp = _i32(tokens)
+        nxt = C.c_int32(-1)
+        self._chk(self.lib.fv_prefill(self.ctx, tp, len(t), C.byref(nxt)), "fv_prefill")
+        self.last_n = len(t) - ((len(t) - 1) // self.max_tree) * self.max_tree   # rows of the last chunk
+        return nxt.value
+
+    def verify_tree(self, tokens, parent, depth):
+        t, tp = _i32(tokens)
+        p, pp = _i32(parent)
+        d, dp = _i32(depth)
+        if not (len(t) == len(p) == len(d)):
+            raise ValueError("tokens, parent and depth must have the same length")
+        a = C.c_int32(-1)
+        nxt = C.c_int32(-1)
+        acc = np.zeros(max(1, len(t)), dtype=np.int32)
+        self._chk(self.lib.fv_verify_tree(self.ctx, tp, pp, dp, len(t), C.byref(a),
+                                          acc.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nxt)), "fv_verify_tree")
+        self.last_n = len(t)
+        return a.value, acc[:a.value].copy(), nxt.value
+
+    def rollback(self, new_len: int, pending_root: int):
+        self._chk(self.lib.fv_rollback(self.ctx, int(new_len), int(pending_root)), "fv_rollback")
+
+    def state(self):
+        a, b = C.c_int32(), C.c_int32()
+        self._chk(self.lib.fv_get_state(self.ctx, C.byref(a), C.byref(b)), "fv_get_state")
+        return a.value, b.value
+
+    # ---- read-back of the last step
+    def tree_mask(self, n=None):
+        n = n or self.last_n
+        out = np.zeros((n, 4), dtype=np.uint64)
+        self._chk(self.lib.fv_get_tree_mask(self.ctx, out.ctypes.data_as(C.POINTER(C.c_uint64)), n), "fv_get_tree_mask")
+        return out
+
+    def logits(self, n=None):
+        n = n or self.last_n
+        out = np.zeros((n, self.shape.vocab), dtype=np.float32)
+        self._chk(self.lib.fv_get_logits(self.ctx, out.ctypes.data_as(C.POINTER(C.c_float)), n), "fv_get_logits")
+        return out
+
+    def argmax(self, n=None):
+        n = n or self.last_n
+        out = np.zeros(n, dtype=np.int32)
+        self._chk(self.lib.fv_get_argmax(self.ctx, out.ctypes.data_as(C.POINTER(C.c_int32)), n), "fv_get_argmax")
+        return out
+
+    def kv_moves(self):
+        src = np.zeros(256, dtype=np.int32)
+        dst = np.zeros(256, dtype=np.int32)
+        cnt = C.c_int32()
+        self._chk(self.lib.fv_get_kv_moves(self.ctx, src.ctypes.data_as(C.POINTER(C.c_int32)),
+                                           dst.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(cnt)), "fv_get_kv_moves")
+        return src[:cnt.value].copy(), dst[:cnt.value].copy()
+
+    def read_kv(self, layer: int, slot0: int, n: int):
+        s = self.shape
+        k = np.zeros((n, s.n_kv_heads, s.head_dim), dtype=np.float32)
+        v = np.zeros_like(k)
+        self._chk(self.lib.fv_read_kv(self.ctx, layer, slot0, n, k.ctypes.data_as(C.POINTER(C.c_float)),
+                                      v.ctypes.data_as(C.POINTER(C.c_float))), "fv_read_kv")
+        return k, v
+
+    def activation(self, which: str, n=None):
+        """Last layer's intermediate: which in x, xb, q, attn, ffn -> [n, features] float32."""
+        s = self.shape
+        idx = ("x", "xb", "q", "attn", "ffn").index(which)
+        feats = (s.hidden, s.hidden, s.n_q_heads * s.head_dim, s.n_q_heads * s.head_dim, s.ffn)[idx]
+        n = n or self.last_n
+        out = np.zeros((n, feats), dtype=np.float32)
+        self._chk(self.lib.fv_debug_read_activation(self.ctx, idx, n, out.ctypes.data_as(C.POINTER(C.c_float))),
+                  "fv_debug_read_activation")
+        return out
+
+    # ---- measurement
+    def set_profiling(self, on: bool):
+        self._chk(self.lib.fv_set_profiling(self.ctx, 1 if on else 0), "fv_set_profiling")
+
+    def phase_times(self):
+        ms = (C.c_float * 4)()
+        n = (C.c_int32 * 4)()
+        self._chk(self.lib.fv_get_phase_times(self.ctx, ms, n), "fv_get_phase_times")
+        return {PHASES[i]: (ms[i], n[i]) for i in range(4)}
+
+    def last_step_ms(self) -> float:
+        v = C.c_float()
+        self._chk(self.lib.fv_last_step_ms(self.ctx, C.byref(v)), "fv_last_step_ms")
+        return v.value
