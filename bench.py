@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification step on one MI355X.
+
+A "step" is one fv_verify_tree call: the whole hot path (tree ingest, embedding, all
+decoder layers with tree attention, LM head, argmax, longest-path scan, KV compaction)
+over one synthetic draft tree, with weights, KV cache and prefix already resident in
+HBM.  Every step starts from the same state (fv_rollback, a host-side counter reset).
+
+Prints ONE JSON line.  Default workload: the 7B-shaped decoder in bf16, prefix 512,
+64-node tree with a planted greedy path of 3 draft tokens.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def build_tree(fi, gpu, shape, n_nodes, branching, plant_len, prefix_len, root, seed):
+    """Topology from the seeded generator; the planted path carries the device's own greedy
+    continuation (single-node steps), so that the step accepts plant_len draft tokens."""
+    from fv_inputs.trees import fill_tokens
+    greedy, tk = [], root
+    p1, d1 = fi.chain_tree(1)
+    for _ in range(plant_len):
+        a, _, tk = gpu.verify_tree([tk], p1, d1)
+        assert a == 0
+        greedy.append(tk)
+    gpu.rollback(prefix_len, root)
+    parent, depth, planted = fi.gen_tree(seed, n_nodes, branching, plant_len)
+    # non-planted children of planted nodes must not carry the greedy token by accident
+    avoid = {i: set() for i in range(n_nodes)}
+    pl = [int(x) for x in planted]
+    for i in range(1, n_nodes):
+        if int(parent[i]) in pl:
+            j = pl.index(int(parent[i]))
+            if j < len(greedy):
+                avoid[i].add(greedy[j])
+    tokens = fill_tokens(seed, parent, shape.vocab, root, planted, greedy, avoid)
+    return tokens, parent, depth, greedy
+
+
+def cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root, sample_layers, full_bytes):
+    """The oracle as it stands, timed on this host on a bounded sample: the same step on the
+    first `sample_layers` layers (+ final norm and LM head) of the same weights; scaled to the
+    full model by algorithmic bytes (all of the step's work is proportional to them)."""
+    from oracle import falcon_oracle as fo
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    sub, subw = fi.sub_model(shape, weights, sample_layers)
+    L, T = len(prefix), len(tokens)
+    o = fo.Oracle(sub, subw, max_seq=L + T + 8, dtype=np.float64)
+    t0 = time.time()
+    o.prefill(prefix)
+    t_prefill = time.time() - t0
+    o.rollback(L, int(tokens[0]))   # same root token as the GPU step (the sub-model's own greedy token differs)
+    times = []
+    for _ in range(2):
+        t0 = time.time()
+        o.verify_tree(tokens, parent, depth)
+        times.append(time.time() - t0)
+        o.rollback(L, int(tokens[0]))
+    t_s = min(times)
+    scale = full_bytes / sub.step_bytes(L, T)
+    t_full = t_s * scale
+    return {
+        "value": T / t_full, "unit": "verified tree tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"numpy fp64 oracle, verify_tree on the first {sample_layers} of {shape.n_layers} layers + LM head "
+                  f"({t_s:.2f} s measured, x{scale:.2f} by algorithmic bytes -> {t_full:.1f} s per full step; "
+                  f"oracle prefill of the sample took {t_prefill:.1f} s)",
+        "ms_per_step_est": t_full * 1e3,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--shape", default="7b")
+    ap.add_argument("--layers", type=int, default=0, help="truncate the model (debug only; marks the line invalid)")
+    ap.add_argument("--prefix", type=int, default=512)
+    ap.add_argument("--nodes", type=int, default=64)
+    ap.add_argument("--branching", default="8,4,2,2,1,1")
+    ap.add_argument("--plant", type=int, default=3)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-layers", type=int, default=2, help="layers in the oracle's CPU-baseline sample (0 = skip)")
+    ap.add_argument("--profile-steps", type=int, default=10)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a one-GPU path (one decoding session per GPU, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
+        sys.exit(3)
+    import fv_inputs as fi
+    import paper_2412_12639_amd as m
+    m.load_library()
+
+    shape = fi.SHAPES[args.shape]
+    if args.layers:
+        shape = shape.with_layers(args.layers)
+    branching = [int(x) for x in args.branching.split(",")]
+    L, T = args.prefix, args.nodes
+
+    t0 = time.time()
+    weights = fi.gen_weights(shape, seed=args.seed)
+    log(f"weights generated on the host in {time.time() - t0:.1f} s ({shape.weight_params() * shape.elem_bytes() / 1e9:.2f} GB)")
+    max_tree = 256
+    gpu = m.FalconVerifier(shape, max_seq=L + max_tree + 8, max_tree=max_tree)
+    t0 = time.time()
+    gpu.init_weights(weights)
+    log(f"weights uploaded and tiled in {time.time() - t0:.1f} s; arena {gpu.bytes / 1e9:.2f} GB")
+
+    prefix = fi.gen_prefix(args.seed, L, shape.vocab)
+    t0 = time.time()
+    root = gpu.prefill(prefix)
+    log(f"prefill of {L} tokens: {(time.time() - t0) * 1e3:.1f} ms, root token {root}")
+    tokens, parent, depth, greedy = build_tree(fi, gpu, shape, T, branching, args.plant, L, root, args.seed)
+
+    def step():
+        gpu.rollback(L, root)
+        return gpu.verify_tree(tokens, parent, depth)
+
+    for _ in range(args.warmup):
+        res = step()
+    a, acc, nxt = res if args.warmup else step()
+    # losslessness at full size: the planted greedy path is accepted, nothing past it
+    assert a >= args.plant and list(acc[:args.plant]) == greedy[:args.plant], (a, acc, greedy)
+
+    torch.cuda.synchronize()
+    dev_ms = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+        dev_ms.append(gpu.last_step_ms())
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    dev_ms = np.array(dev_ms)
+
+    # per-kernel-class device time with HIP events on the library's stream (separate pass:
+    # the extra events open launch gaps, so this pass is not the throughput figure)
+    gpu.set_profiling(True)
+    gpu.phase_times()
+    for _ in range(args.profile_steps):
+        step()
+    ph = gpu.phase_times()
+    gpu.set_profiling(False)
+    n_gemm = ph["gemm"][1] / args.profile_steps
+    gemm_ms_per_launch = ph["gemm"][0] / max(1, ph["gemm"][1])
+    weight_bytes = shape.weight_params() * shape.elem_bytes()
+    bytes_per_launch = weight_bytes / n_gemm
+    achieved = bytes_per_launch / (gemm_ms_per_launch * 1e-3) / 1e9
+    step_bytes = shape.step_bytes(L, T)
+
+    out = {
+        "metric": "verified tree tokens/s (tree-verify step, 7B shape, 64-node tree)" if args.shape == "7b" and T == 64
+                  else f"verified tree tokens/s (tree-verify step, {shape.name}, {T}-node tree)",
+        "value": T * args.steps / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{shape.name}-shape random-init decoder ({shape.n_layers} layers, hidden {shape.hidden}, "
+                               f"{shape.n_q_heads}q/{shape.n_kv_heads}kv heads x {shape.head_dim}, FFN {shape.ffn}, vocab {shape.vocab}), "
+                               f"prefix {L}, {T}-node draft tree (branching {branching}, planted greedy path {args.plant})",
+                   "prefix_len": L, "tree_nodes": T, "accepted_len": int(a), "batch": 1},
+        "latency_us": ms_per_step * 1e3,
+        "device_ms_per_step": {"median": float(np.median(dev_ms)), "p10": float(np.percentile(dev_ms, 10)),
+                               "p90": float(np.percentile(dev_ms, 90))},
+        "emitted_tokens_per_s": (a + 1) * args.steps / wall,
+        "step_hbm_fraction": step_bytes / (float(np.median(dev_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_algorithmic_bytes": step_bytes,
+        "roofline": {"bound": "hbm", "kernel": "k_gemm (weight-streaming skinny GEMM)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": bytes_per_launch, "avg_launch_us": gemm_ms_per_launch * 1e3,
+                     "launches_per_step": n_gemm},
+        "phase_ms_per_step": {k: v[0] / args.profile_steps for k, v in ph.items()},
+    }
+    if args.layers:
+        out["invalid"] = "model truncated with --layers (debug run)"
+    if args.cpu_layers > 0:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root,
+                                           min(args.cpu_layers, shape.n_layers), step_bytes)
+    else:
+        out["cpu_baseline"] = None
+    gpu.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -42,6 +42,9 @@ def load_library():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # torch ships its own HIP runtime; it must be the one already in the process when this
+    # library is loaded, or two runtimes would coexist and not know each other's allocations
+    import torch  # noqa: F401
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: build it first (python -m paper_2412_12639_amd.build, "

@@ -138,7 +138,7 @@ def test_multi_chunk_prefill_and_multi_step_decode(fvmod, name):
     tol = H.tol_for(s)
     say("multi", name)
     L0 = 2 * 32 + 7
-    prefix = fi.gen_prefix(11, L0, s.vocab)
+    prefix = fi.gen_prefix(13, L0, s.vocab)   # a prompt after which five steps in a row have clear argmax gaps
     o = fo.Oracle(s, w, max_seq=L0 + 200)
     root = o.prefill(prefix)
     g = make_gpu(fvmod, s, w, max_seq=L0 + 200, max_tree=32)
@@ -162,12 +162,19 @@ def test_multi_chunk_prefill_and_multi_step_decode(fvmod, name):
             p1, d1 = fi.chain_tree(1)
             tk = o.verify_tree(np.array([tk], dtype=np.int32), p1, d1)["next_token"]
             greedy.append(tk)
-        o.rollback(L, g.state()[1])
-        parent, depth, planted = fi.gen_tree(100 + step, 24, [3, 3, 2, 2, 1], plant)
-        tokens = fill_tokens(100 + step, parent, s.vocab, o.pending, planted, greedy)
-        res = o.verify_tree(tokens, parent, depth)
-        if not H.decision_margins_ok(res, tokens, parent, tol):
-            say("step", step, "margins inside tolerance band: stop here")
+        pending = g.state()[1]
+        for attempt in range(30):   # a tree whose decisive argmax gaps clear the tolerance
+            o.rollback(L, pending)
+            sd = 100 + step + 50 * attempt
+            parent, depth, planted = fi.gen_tree(sd, 24, [3, 3, 2, 2, 1], plant)
+            tokens = fill_tokens(sd, parent, s.vocab, pending, planted, greedy)
+            res = o.verify_tree(tokens, parent, depth)
+            if H.decision_margins_ok(res, tokens, parent, tol):
+                break
+        else:
+            # the greedy path itself has a near-tie here: nothing decisive can be demanded past this point
+            o.rollback(L, pending)
+            say("step", step, "near-tie on the greedy path: stop here")
             break
         a, acc, nxt = g.verify_tree(tokens, parent, depth)
         case = dict(res=res, parent=parent)
@@ -176,7 +183,7 @@ def test_multi_chunk_prefill_and_multi_step_decode(fvmod, name):
         emitted_g += list(acc) + [nxt]
         emitted_o += list(res["accepted_tokens"]) + [res["next_token"]]
         assert g.state() == (o.L, o.pending)
-    assert emitted_g == emitted_o and len(emitted_g) >= 1
+    assert emitted_g == emitted_o and step >= 4 and len(emitted_g) >= 5
     e = H.check_cache(g, o, s, o.L, tol)
     say("final cache err", e)
     g.close()
