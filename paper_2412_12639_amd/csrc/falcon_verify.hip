@@ -30,19 +30,21 @@ struct GemmPlan {
     int n_strips = 0, n_strips_pad = 0, NG = 0;
     int G = 0, segmax = 0;
     size_t tiled_bytes = 0;
+    size_t off_tab = 0;   // device tables: u0[G+1], g0[G], cf[NG], cl[NG]
 };
 
 enum { GM_QKV = 0, GM_O = 1, GM_GU = 2, GM_DN = 3, GM_LM = 4, GM_COUNT = 5 };
 
 struct Layout {
     int E = 0, ESZ = 0, Tpm = 0, S_pad = 0, Vpad = 0;
-    GemmPlan gm[GM_COUNT];
+    GemmPlan gm[GM_COUNT];    // shared-activation kernel (row groups of FV_R strips)
+    GemmPlan gd[GM_COUNT];    // direct kernel (one strip per workgroup at a time), used up to 64 tokens
     size_t layer_w_bytes = 0;        // tiled weights of one layer
     size_t off_w[4] = {0, 0, 0, 0};  // offsets of QKV, O, GU, DN inside a layer
     size_t off_layers = 0, off_lm = 0, off_embed = 0, off_gains = 0;
     size_t off_k = 0, off_v = 0, kv_layer_bytes = 0;
     size_t off_x = 0, off_xb = 0, off_q = 0, off_attn = 0, off_act = 0, off_logits = 0;
-    size_t off_ssq = 0, off_rinv = 0, off_part = 0, part_bytes = 0;
+    size_t off_ssq = 0, off_rinv = 0, off_part = 0, part_bytes = 0, off_tickets = 0;
     size_t off_stepin = 0, off_mask = 0, off_pos = 0, off_rope = 0, off_am = 0, off_res = 0;
     size_t off_kvread = 0, off_stage = 0, stage_bytes = 0;
     size_t total = 0;
@@ -68,19 +70,38 @@ int pad_tokens(int n) {   // token count padded to 32, 64, 128 or 256
     return tp;
 }
 
-void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg) {
+void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R) {
     const int KB = 16 * E;
     p.K = K;
     p.Kpad = (int)rup(K, KB);
     p.NB = p.Kpad / KB;
     p.n_strips = n_strips;
-    p.n_strips_pad = (int)rup(n_strips, FV_R);
-    p.NG = p.n_strips_pad / FV_R;
+    p.n_strips_pad = (int)rup(n_strips, FV_R);   // the tiled buffer always holds whole groups of FV_R strips
+    p.NG = (R == 1) ? n_strips : p.n_strips_pad / R;
     const long long U = (long long)p.NG * p.NB;
     p.G = (int)(U < n_wg ? U : n_wg);
     const long long per = (U + p.G - 1) / p.G;
     p.segmax = (int)((per + p.NB - 1) / p.NB) + 1;
     p.tiled_bytes = (size_t)p.n_strips_pad * p.NB * FV_FRAGS * 1024;
+}
+
+// The stream-K split of one GEMM: workgroup w owns units [u0[w], u0[w+1]) of the (row group,
+// K batch) space; g0[w] is its first row group; row group gi is shared by workgroups cf[gi]..cl[gi].
+void build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
+    const long long U = (long long)p.NG * p.NB;
+    tab.assign((size_t)2 * p.G + 1 + 2 * p.NG, 0);
+    int* u0 = tab.data();
+    int* g0 = u0 + p.G + 1;
+    int* cf = g0 + p.G;
+    int* cl = cf + p.NG;
+    for (int w = 0; w <= p.G; ++w) u0[w] = (int)(U * w / p.G);
+    for (int w = 0; w < p.G; ++w) g0[w] = u0[w] / p.NB;
+    for (int gi = 0; gi < p.NG; ++gi) { cf[gi] = p.G; cl[gi] = -1; }
+    for (int w = 0; w < p.G; ++w)
+        for (int gi = g0[w]; gi <= (u0[w + 1] - 1) / p.NB; ++gi) {
+            if (w < cf[gi]) cf[gi] = w;
+            if (w > cl[gi]) cl[gi] = w;
+        }
 }
 
 void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
@@ -94,6 +115,7 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     plan_gemm(L.gm[GM_GU], c.ffn / 16, c.hidden, L.E, n_wg);
     plan_gemm(L.gm[GM_DN], c.hidden / 32, c.ffn, L.E, n_wg);
     plan_gemm(L.gm[GM_LM], (c.vocab + 31) / 32, c.hidden, L.E, n_wg);
+    for (int i = 0; i < GM_COUNT; ++i) plan_gemm(L.gd[i], L.gm[i].n_strips, L.gm[i].K, L.E, n_wg, 1);
     L.Vpad = L.gm[GM_LM].n_strips * 32;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o = rup(o + bytes, 256); return r; };
@@ -120,9 +142,18 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     for (int i = 0; i < GM_COUNT; ++i) {
         const size_t b = (size_t)L.gm[i].G * L.gm[i].segmax * FV_R * (T / 32) * 4096;
         if (b > pb) pb = b;
+        const size_t bd = (size_t)L.gd[i].G * L.gd[i].segmax * 2 * 4096;
+        if (bd > pb) pb = bd;
     }
     L.part_bytes = pb;
     L.off_part = take(pb);
+    int ngmax = 0;
+    for (int i = 0; i < GM_COUNT; ++i) if (L.gm[i].n_strips_pad > ngmax) ngmax = L.gm[i].n_strips_pad;
+    L.off_tickets = take((size_t)ngmax * 4);
+    for (int i = 0; i < GM_COUNT; ++i) {
+        L.gm[i].off_tab = take((size_t)(2 * L.gm[i].G + 1 + 2 * L.gm[i].NG) * 4);
+        L.gd[i].off_tab = take((size_t)(2 * L.gd[i].G + 1 + 2 * L.gd[i].NG) * 4);
+    }
     L.off_stepin = take(3 * FV_MAX_TREE * 4);
     L.off_mask = take(FV_MAX_TREE * 4 * 8);
     L.off_pos = take(FV_MAX_TREE * 4);
@@ -172,6 +203,7 @@ struct fv_ctx {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     float last_ms = 0.f;
     bool profiling = false;
+    bool force_shared = false;   // FV_GEMM=shared: use the LDS-shared kernel for every token count (tuning)
     std::vector<hipEvent_t> pev;       // event pool for profiling
     std::vector<int> pev_phase;        // phase of each (start, stop) pair
     size_t pev_used = 0;
@@ -203,37 +235,49 @@ struct PhaseTimer {   // brackets launches with events when profiling is on
     ~PhaseTimer() { if (on) (void)hipEventRecord(c->pev[idx + 1], c->stream); }
 };
 
-template <typename EL, int TB>
+template <typename EL, int TB, int D, int EPI>
 int launch_gemm_t(fv_ctx* c, const GemmArgs& ga) {
     const size_t lds = (size_t)2 * TB * 32 * 256;
-    hipLaunchKernelGGL((k_gemm<EL, TB>), dim3(ga.G), dim3(64 * FV_R), lds, c->stream, ga);
+    hipLaunchKernelGGL((k_gemm<EL, TB, D, EPI>), dim3(ga.G), dim3(64 * FV_R), lds, c->stream, ga);
     return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
 }
 
-template <typename EL>
-int launch_gemm(fv_ctx* c, int Tp, const GemmArgs& ga) {
+template <typename EL, int TB, int D, int EPI>
+int launch_gemm_direct_t(fv_ctx* c, const GemmArgs& ga) {
+    hipLaunchKernelGGL((k_gemm_direct<EL, TB, D, EPI>), dim3(ga.G), dim3(256), 0, c->stream, ga);
+    return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
+}
+
+template <typename EL, int D, int EPI>
+int launch_gemm(fv_ctx* c, int Tp, const GemmArgs& ga, bool direct) {
+    if (direct) return Tp == 32 ? launch_gemm_direct_t<EL, 1, D, EPI>(c, ga) : launch_gemm_direct_t<EL, 2, D, EPI>(c, ga);
     switch (Tp) {
-        case 32: return launch_gemm_t<EL, 1>(c, ga);
-        case 64: return launch_gemm_t<EL, 2>(c, ga);
-        case 128: return launch_gemm_t<EL, 4>(c, ga);
-        case 256: return launch_gemm_t<EL, 8>(c, ga);
+        case 32: return launch_gemm_t<EL, 1, D, EPI>(c, ga);
+        case 64: return launch_gemm_t<EL, 2, D, EPI>(c, ga);
+        case 128: return launch_gemm_t<EL, 4, D, EPI>(c, ga);
+        case 256: return launch_gemm_t<EL, 8, D, EPI>(c, ga);
     }
     return FV_E_BAD_ARG;
 }
 
-template <typename EL>
-int set_gemm_attrs() {
+template <typename EL, int D, int EPI>
+int set_gemm_attrs_e() {
     // the 256-token instantiation double-buffers 2 x 64 KiB of activations in LDS
-    HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 256 * 256));
-    HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 256));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 8, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 256 * 256));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 4, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 256));
     return FV_OK;
 }
-
-template <typename EL, int D, int EPI>
-int launch_fixup(fv_ctx* c, const FixArgs& fa) {
-    const int waves = fa.n_strips * (fa.Tp / 32);
-    hipLaunchKernelGGL((k_fixup<EL, D, EPI>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, fa);
-    return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
+template <typename EL, int D>
+int set_gemm_attrs_d() {
+    int rc = set_gemm_attrs_e<EL, D, EPI_QKV>();
+    if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_RESID>();
+    if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_SWIGLU>();
+    if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_LOGITS>();
+    return rc;
+}
+template <typename EL>
+int set_gemm_attrs(int head_dim) {
+    return head_dim == 128 ? set_gemm_attrs_d<EL, 128>() : set_gemm_attrs_d<EL, 64>();
 }
 
 enum StepMode { STEP_VERIFY = 0, STEP_PREFILL_MID = 1, STEP_PREFILL_LAST = 2 };
@@ -266,37 +310,28 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
     }
     HIPCHK(hipGetLastError());
 
-    auto gemm = [&](int which, const void* Wt, size_t x_off, bool norm_in) -> int {
-        PhaseTimer pt(c, FV_PH_GEMM);
-        const GemmPlan& p = ly.gm[which];
+    const bool direct = (Tp <= 64) && !c->force_shared;
+    auto gemm_args = [&](int which, const void* Wt, size_t x_off) {
+        const GemmPlan& p = direct ? ly.gd[which] : ly.gm[which];
         GemmArgs ga;
+        memset(&ga, 0, sizeof(ga));
         ga.Wt = (const uint4*)Wt; ga.X = c->at<uint4>(x_off); ga.part = c->at<float>(ly.off_part);
+        ga.tickets = c->at<int>(ly.off_tickets);
         ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax;
-        ga.ssq_part = norm_in ? c->at<float>(ly.off_ssq) : nullptr;
-        ga.rinv = c->at<float>(ly.off_rinv); ga.n_ssq = h / 32; ga.inv_h = 1.f / (float)h; ga.eps = cf.rms_eps;
-        return launch_gemm<EL>(c, Tp, ga);
-    };
-    auto fix_base = [&](int which) {
-        const GemmPlan& p = ly.gm[which];
-        FixArgs fa;
-        memset(&fa, 0, sizeof(fa));
-        fa.part = c->at<float>(ly.off_part);
-        fa.NG = p.NG; fa.NB = p.NB; fa.G = p.G; fa.segmax = p.segmax;
-        fa.Tp = Tp; fa.T = T; fa.n_strips = p.n_strips;
-        fa.rinv = c->at<float>(ly.off_rinv);
-        return fa;
+        ga.tab_u0 = c->at<int>(p.off_tab); ga.tab_g0 = ga.tab_u0 + p.G + 1; ga.tab_cf = ga.tab_g0 + p.G; ga.tab_cl = ga.tab_cf + p.NG;
+        ga.T = T; ga.n_strips = p.n_strips;
+        ga.ssq_in = c->at<float>(ly.off_ssq); ga.n_ssq = h / 32; ga.inv_h = 1.f / (float)h; ga.eps = cf.rms_eps;
+        return ga;
     };
 
     for (int l = 0; l < cf.n_layers; ++l) {
-        // q, k, v projections of the normalised input, rotary at pos = L + depth, K/V to cache slots L + i
-        int rc = gemm(GM_QKV, c->layer_w(l, 0), ly.off_xb, true);
-        if (rc) return rc;
-        {
-            PhaseTimer pt(c, FV_PH_FIXUP);
-            FixArgs fa = fix_base(GM_QKV);
-            fa.q_out = c->at<void>(ly.off_q); fa.kcache = c->kc(l); fa.vcache = c->vc(l);
-            fa.rope_cs = c->at<float2>(ly.off_rope); fa.Hq = cf.n_q_heads; fa.Hkv = cf.n_kv_heads; fa.L = L; fa.S_pad = ly.S_pad;
-            rc = launch_fixup<EL, D, EPI_QKV>(c, fa);
+        int rc;
+        {   // q, k, v projections of the normalised input, rotary at pos = L + depth, K/V to cache slots L + i
+            PhaseTimer pt(c, FV_PH_GEMM);
+            GemmArgs ga = gemm_args(GM_QKV, c->layer_w(l, 0), ly.off_xb);
+            ga.q_out = c->at<void>(ly.off_q); ga.kcache = c->kc(l); ga.vcache = c->vc(l);
+            ga.rope_cs = c->at<float2>(ly.off_rope); ga.Hq = cf.n_q_heads; ga.Hkv = cf.n_kv_heads; ga.L = L; ga.S_pad = ly.S_pad;
+            rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, direct);
             if (rc) return rc;
         }
         {
@@ -309,46 +344,38 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             hipLaunchKernelGGL((k_attn<EL, D>), dim3(cf.n_q_heads * (Tp / 32)), dim3(256), 0, st, aa);
             HIPCHK(hipGetLastError());
         }
-        rc = gemm(GM_O, c->layer_w(l, 1), ly.off_attn, false);
-        if (rc) return rc;
-        {
-            PhaseTimer pt(c, FV_PH_FIXUP);
-            FixArgs fa = fix_base(GM_O);
-            fa.x = c->at<float>(ly.off_x); fa.xb = c->at<void>(ly.off_xb); fa.gain_next = c->gain(2 * l + 1);
-            fa.ssq_part = c->at<float>(ly.off_ssq);
-            rc = launch_fixup<EL, D, EPI_RESID>(c, fa);
+        {   // output projection, residual add, statistics + input of the FFN norm
+            PhaseTimer pt(c, FV_PH_GEMM);
+            GemmArgs ga = gemm_args(GM_O, c->layer_w(l, 1), ly.off_attn);
+            ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb); ga.gain_next = c->gain(2 * l + 1);
+            ga.ssq_out = c->at<float>(ly.off_ssq);
+            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, direct);
             if (rc) return rc;
         }
-        rc = gemm(GM_GU, c->layer_w(l, 2), ly.off_xb, true);
-        if (rc) return rc;
-        {
-            PhaseTimer pt(c, FV_PH_FIXUP);
-            FixArgs fa = fix_base(GM_GU);
-            fa.act = c->at<void>(ly.off_act);
-            rc = launch_fixup<EL, D, EPI_SWIGLU>(c, fa);
+        {   // gate and up projections, SwiGLU
+            PhaseTimer pt(c, FV_PH_GEMM);
+            GemmArgs ga = gemm_args(GM_GU, c->layer_w(l, 2), ly.off_xb);
+            ga.act = c->at<void>(ly.off_act);
+            rc = launch_gemm<EL, D, EPI_SWIGLU>(c, Tp, ga, direct);
             if (rc) return rc;
         }
-        rc = gemm(GM_DN, c->layer_w(l, 3), ly.off_act, false);
-        if (rc) return rc;
-        {
-            PhaseTimer pt(c, FV_PH_FIXUP);
-            FixArgs fa = fix_base(GM_DN);
-            fa.x = c->at<float>(ly.off_x); fa.xb = c->at<void>(ly.off_xb);
-            fa.gain_next = (l + 1 < cf.n_layers) ? c->gain(2 * (l + 1)) : c->gain(2 * cf.n_layers);
-            fa.ssq_part = c->at<float>(ly.off_ssq);
-            rc = launch_fixup<EL, D, EPI_RESID>(c, fa);
+        {   // down projection, residual add, statistics + input of the next norm
+            PhaseTimer pt(c, FV_PH_GEMM);
+            GemmArgs ga = gemm_args(GM_DN, c->layer_w(l, 3), ly.off_act);
+            ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb);
+            ga.gain_next = (l + 1 < cf.n_layers) ? c->gain(2 * (l + 1)) : c->gain(2 * cf.n_layers);
+            ga.ssq_out = c->at<float>(ly.off_ssq);
+            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, direct);
             if (rc) return rc;
         }
     }
 
     if (mode != STEP_PREFILL_MID) {
-        int rc = gemm(GM_LM, c->at<void>(ly.off_lm), ly.off_xb, true);
-        if (rc) return rc;
         {
-            PhaseTimer pt(c, FV_PH_FIXUP);
-            FixArgs fa = fix_base(GM_LM);
-            fa.logits = c->at<float>(ly.off_logits); fa.Vpad = ly.Vpad;
-            rc = launch_fixup<EL, D, EPI_LOGITS>(c, fa);
+            PhaseTimer pt(c, FV_PH_GEMM);
+            GemmArgs ga = gemm_args(GM_LM, c->at<void>(ly.off_lm), ly.off_xb);
+            ga.logits = c->at<float>(ly.off_logits); ga.Vpad = ly.Vpad;
+            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, direct);
             if (rc) return rc;
         }
         PhaseTimer pt(c, FV_PH_OTHER);
@@ -524,6 +551,7 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     if (arena_bytes < c->lay.total) { delete c; return FV_E_BAD_ARG; }
     c->arena = (char*)dev_arena;
     c->stream = (hipStream_t)hip_stream;
+    { const char* e = getenv("FV_GEMM"); c->force_shared = e && !strcmp(e, "shared"); }
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipHostMalloc((void**)&c->h_res, sizeof(FvResult), hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
@@ -533,7 +561,13 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     const size_t z0 = c->lay.off_gains;
     if (hipMemsetAsync(c->arena + z0, 0, c->lay.total - z0, c->stream) != hipSuccess) return fail(FV_E_HIP);
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(FV_E_HIP);
-    rc = (cfg->dtype == FV_BF16) ? set_gemm_attrs<BF16>() : set_gemm_attrs<F32>();
+    for (int k = 0; k < 2 * GM_COUNT; ++k) {
+        const GemmPlan& p = (k < GM_COUNT) ? c->lay.gm[k] : c->lay.gd[k - GM_COUNT];
+        std::vector<int> tab;
+        build_split_tables(p, tab);
+        if (hipMemcpy(c->arena + p.off_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return fail(FV_E_HIP);
+    }
+    rc = (cfg->dtype == FV_BF16) ? set_gemm_attrs<BF16>(cfg->head_dim) : set_gemm_attrs<F32>(cfg->head_dim);
     if (rc) return fail(rc);
     *out = c;
     return FV_OK;

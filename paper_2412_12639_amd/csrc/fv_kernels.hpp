@@ -93,199 +93,69 @@ __global__ void k_embed(EmbedArgs a) {
 // space is cut into G equal contiguous ranges, one per workgroup (stream-K), so all CUs
 // stream the same number of bytes whatever N and K are.  A workgroup is R wavefronts;
 // wavefront w owns strip w of the row group and all of them share the X chunk in LDS.
-// Each range piece that lies in one row group is a "segment" whose fp32 accumulators go
-// to `part`; k_fixup sums the segments of a row group in a fixed order (deterministic)
-// and applies the epilogue.
+// Each range piece that lies in one row group is a "segment".  A segment that covers the
+// whole K range goes straight from registers to the epilogue; otherwise its fp32
+// accumulators go to `part`, the workgroup takes a ticket on the row group's counter, and
+// the workgroup that draws the last ticket sums all segments of the group in ascending
+// workgroup order (so the result does not depend on who arrives last) and runs the epilogue.
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+
 struct GemmArgs {
     const uint4* Wt;     // tiled weights [NG*R strips][NB][FRAGS][64] x 16 B
     const uint4* X;      // vector-major [NB*16][Tp] x 16 B
     float* part;         // [G][segmax][R][TB][64][16] fp32
+    int* tickets;        // [NG], zero on entry, left zero on exit
     int NG, NB, G, segmax;
-    // side job of workgroup 0: finish the RMSNorm statistics of the input
-    const float* ssq_part;   // [n_ssq][Tp] or null
-    float* rinv;             // [Tp]
+    // stream-K split, precomputed on the host: range start of every workgroup (G+1 entries), its
+    // first row group, and the first / last contributing workgroup of every row group
+    const int* tab_u0; const int* tab_g0; const int* tab_cf; const int* tab_cl;
+    int T, n_strips;     // real tokens; strips that carry real rows
+    // RMSNorm statistics of the input (QKV, SWIGLU, LOGITS): rinv[t] = rsqrt(sum_s ssq_in[s][t] / h + eps)
+    const float* ssq_in; // [n_ssq][Tp]
     int n_ssq;
     float inv_h, eps;
-};
-
-template <typename EL, int TB>
-__device__ __forceinline__ void gemm_compute(const uint4 (&w)[FV_FRAGS], const uint4* __restrict__ xl,
-                                             floatx16 (&acc)[TB], int lane) {
-    constexpr int Tp = TB * 32;
-    const int t = lane & 31, g = lane >> 5;
-#pragma unroll
-    for (int f = 0; f < FV_FRAGS; ++f) {
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb) {
-            const uint4 b = xl[(2 * f + g) * Tp + tb * 32 + t];
-            acc[tb] = Tr<EL>::mma(w[f], b, acc[tb]);
-        }
-    }
-}
-
-template <typename EL, int TB>
-__global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
-    extern __shared__ uint4 lds[];
-    constexpr int R = FV_R;
-    constexpr int Tp = TB * 32;
-    constexpr int CV = Tp * 16;          // uint4 per X chunk (Tp tokens x 256 B)
-    constexpr int XV = CV / (64 * R);    // uint4 per thread per chunk
-    static_assert(CV % (64 * R) == 0, "chunk must divide over the workgroup");
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-
-    if (blockIdx.x == 0 && a.ssq_part != nullptr) {
-        for (int t = tid; t < Tp; t += 64 * R) {
-            float s = 0.f;
-            for (int i = 0; i < a.n_ssq; ++i) s += a.ssq_part[(size_t)i * Tp + t];
-            a.rinv[t] = rsqrtf(s * a.inv_h + a.eps);
-        }
-    }
-    if ((int)blockIdx.x >= a.G) return;
-
-    const long long U = (long long)a.NG * a.NB;
-    long long u0 = U * blockIdx.x / a.G;
-    const long long u1 = U * (blockIdx.x + 1) / a.G;
-    int seg = 0;
-    while (u0 < u1) {
-        const int gi = (int)(u0 / a.NB);
-        const int b0 = (int)(u0 - (long long)gi * a.NB);
-        const int nb = (int)((u1 - u0 < (long long)(a.NB - b0)) ? (u1 - u0) : (long long)(a.NB - b0));
-
-        floatx16 acc[TB];
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tb][i] = 0.f;
-
-        const uint4* __restrict__ wp = a.Wt + ((size_t)(gi * R + wave) * a.NB + b0) * (FV_FRAGS * 64) + lane;
-        const uint4* __restrict__ xp = a.X + (size_t)b0 * CV + tid;
-        uint4 w0[FV_FRAGS], w1[FV_FRAGS], xr[XV];
-#pragma unroll
-        for (int f = 0; f < FV_FRAGS; ++f) w0[f] = wp[f * 64];
-#pragma unroll
-        for (int v = 0; v < XV; ++v) xr[v] = xp[v * 64 * R];
-#pragma unroll
-        for (int v = 0; v < XV; ++v) lds[tid + v * 64 * R] = xr[v];
-        __syncthreads();
-
-        for (int b = 0; b < nb; b += 2) {
-            // the next X chunk is always fetched (the last one twice: it is an L2 hit) so that
-            // its staging registers are written and read unconditionally
-            const bool has1 = b + 1 < nb;
-            const int bx1 = has1 ? b + 1 : b;
-#pragma unroll
-            for (int v = 0; v < XV; ++v) xr[v] = xp[(size_t)bx1 * CV + v * 64 * R];
-            if (has1) {
-#pragma unroll
-                for (int f = 0; f < FV_FRAGS; ++f) w1[f] = wp[(size_t)(b + 1) * (FV_FRAGS * 64) + f * 64];
-            }
-            gemm_compute<EL, TB>(w0, lds, acc, lane);
-#pragma unroll
-            for (int v = 0; v < XV; ++v) lds[CV + tid + v * 64 * R] = xr[v];
-            __syncthreads();
-            if (!has1) break;
-            const bool has2 = b + 2 < nb;
-            const int bx2 = has2 ? b + 2 : b + 1;
-#pragma unroll
-            for (int v = 0; v < XV; ++v) xr[v] = xp[(size_t)bx2 * CV + v * 64 * R];
-            if (has2) {
-#pragma unroll
-                for (int f = 0; f < FV_FRAGS; ++f) w0[f] = wp[(size_t)(b + 2) * (FV_FRAGS * 64) + f * 64];
-            }
-            gemm_compute<EL, TB>(w1, lds + CV, acc, lane);
-#pragma unroll
-            for (int v = 0; v < XV; ++v) lds[tid + v * 64 * R] = xr[v];
-            __syncthreads();
-        }
-
-        float4* pp = (float4*)a.part + ((((size_t)blockIdx.x * a.segmax + seg) * R + wave) * TB) * (64 * 4) + lane * 4;
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                pp[tb * 64 * 4 + q] = make_float4(acc[tb][4 * q], acc[tb][4 * q + 1], acc[tb][4 * q + 2], acc[tb][4 * q + 3]);
-        ++seg;
-        u0 += nb;
-    }
-}
-
-// ============================================================================ fix-up + epilogues
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
-
-struct FixArgs {
-    const float* part;
-    int NG, NB, G, segmax;
-    int Tp, T, n_strips;       // n_strips = strips that carry real rows
-    const float* rinv;         // [Tp] RMSNorm factor of the GEMM input (QKV, SWIGLU, LOGITS)
-    // EPI_QKV: rotate q and k at pos = L + depth, write q (vector-major), k and v into the cache at slot L + t
+    // EPI_QKV: rotate q and k, write q (vector-major), k and v into the cache at slot L + t
     void* q_out;
-    void* kcache;              // this layer's K slabs [Hkv][S_pad*D]
+    void* kcache;        // this layer's K slabs [Hkv][S_pad*D]
     void* vcache;
-    const float2* rope_cs;     // [Tp][D/2]
+    const float2* rope_cs;   // [Tp][D/2]
     int Hq, Hkv, L, S_pad;
     // EPI_RESID: x += y; xb = x * gain_next; partial sums of squares of the new x
     float* x;
     void* xb;
     const float* gain_next;
-    float* ssq_part;
+    float* ssq_out;      // [n_strips][Tp]
     // EPI_SWIGLU: act = silu(gate) * up
     void* act;
     // EPI_LOGITS
-    float* logits;             // [Tp][Vpad]
+    float* logits;       // [Tp][Vpad]
     int Vpad;
 };
 
+// Epilogue of one 32-row strip x 32-token block, in accumulator layout: lane (tl, g), acc[i] is
+// row 8*(i/4) + 4*g + i%4 of the strip for token tb*32 + tl.
 template <typename EL, int D, int EPI>
-__global__ __launch_bounds__(256) void k_fixup(FixArgs a) {
-    constexpr int R = FV_R;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int TB = a.Tp >> 5;
-    const int id = blockIdx.x * 4 + wave;
-    const int strip = id / TB, tb = id % TB;
-    if (strip >= a.n_strips) return;
-    const int gi = strip / R, r = strip % R;
-
-    // ---- sum the segments of row group gi, in ascending workgroup order
-    const long long U = (long long)a.NG * a.NB;
-    const long long lo = (long long)gi * a.NB, hi = lo + a.NB;
-    int wg = (int)(lo * a.G / U);
-    while (wg < a.G && U * (wg + 1) / a.G <= lo) ++wg;
-    float acc[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    for (; wg < a.G; ++wg) {
-        const long long w0 = U * wg / a.G, w1 = U * (wg + 1) / a.G;
-        if (w0 >= hi) break;
-        if (w0 == w1) continue;
-        const int seg = gi - (int)(w0 / a.NB);
-        const float4* pp = (const float4*)a.part + ((((size_t)wg * a.segmax + seg) * R + r) * TB + tb) * (64 * 4) + lane * 4;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float4 v = pp[q];
-            acc[4 * q] += v.x; acc[4 * q + 1] += v.y; acc[4 * q + 2] += v.z; acc[4 * q + 3] += v.w;
-        }
-    }
-
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
+                                              const float* rinv_lds) {
     const int tl = lane & 31, g = lane >> 5;
     const int t = tb * 32 + tl;
-
     if constexpr (EPI == EPI_RESID) {
         float ssq = 0.f;
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk) {
             const int f0 = strip * 32 + 8 * blk + 4 * g;
-            float4* xp = (float4*)a.x + (size_t)(f0 >> 2) * a.Tp + t;
+            float4* xp = (float4*)a.x + (size_t)(f0 >> 2) * Tp + t;
             float4 xv = *xp;
             xv.x += acc[4 * blk]; xv.y += acc[4 * blk + 1]; xv.z += acc[4 * blk + 2]; xv.w += acc[4 * blk + 3];
             *xp = xv;
-            store4_act<EL>(a.xb, a.Tp, f0, t, xv.x * a.gain_next[f0], xv.y * a.gain_next[f0 + 1],
+            store4_act<EL>(a.xb, Tp, f0, t, xv.x * a.gain_next[f0], xv.y * a.gain_next[f0 + 1],
                            xv.z * a.gain_next[f0 + 2], xv.w * a.gain_next[f0 + 3]);
             ssq += xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
         }
         ssq += __shfl_xor(ssq, 32);
-        if (g == 0) a.ssq_part[(size_t)strip * a.Tp + t] = ssq;
+        if (g == 0) a.ssq_out[(size_t)strip * Tp + t] = ssq;
     } else {
-        const float rs = a.rinv[t];
+        const float rs = rinv_lds[t];
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] *= rs;
         if constexpr (EPI == EPI_LOGITS) {
@@ -306,7 +176,7 @@ __global__ __launch_bounds__(256) void k_fixup(FixArgs a) {
                     const float gt = acc[8 * pr + c], up = acc[8 * pr + 4 + c];
                     o[c] = gt / (1.f + __expf(-gt)) * up;
                 }
-                store4_act<EL>(a.act, a.Tp, 16 * strip + 8 * pr + 4 * g, t, o[0], o[1], o[2], o[3]);
+                store4_act<EL>(a.act, Tp, 16 * strip + 8 * pr + 4 * g, t, o[0], o[1], o[2], o[3]);
             }
         } else {  // EPI_QKV
             constexpr int SPH = D / 32;   // strips per head
@@ -328,8 +198,8 @@ __global__ __launch_bounds__(256) void k_fixup(FixArgs a) {
 #pragma unroll
                     for (int pr = 0; pr < 2; ++pr) {
                         const int f1 = head * D + 16 * j + 8 * pr + 4 * g;
-                        store4_act<EL>(a.q_out, a.Tp, f1, t, lo_v[pr][0], lo_v[pr][1], lo_v[pr][2], lo_v[pr][3]);
-                        store4_act<EL>(a.q_out, a.Tp, f1 + D / 2, t, hi_v[pr][0], hi_v[pr][1], hi_v[pr][2], hi_v[pr][3]);
+                        store4_act<EL>(a.q_out, Tp, f1, t, lo_v[pr][0], lo_v[pr][1], lo_v[pr][2], lo_v[pr][3]);
+                        store4_act<EL>(a.q_out, Tp, f1 + D / 2, t, hi_v[pr][0], hi_v[pr][1], hi_v[pr][2], hi_v[pr][3]);
                     }
                 } else if (t < a.T) {
                     const int kh = head - a.Hq;
@@ -357,6 +227,247 @@ __global__ __launch_bounds__(256) void k_fixup(FixArgs a) {
         }
     }
 }
+
+template <typename EL, int TB>
+__device__ __forceinline__ void gemm_compute(const uint4 (&w)[FV_FRAGS], const uint4* __restrict__ xl,
+                                             floatx16 (&acc)[TB], int lane) {
+    constexpr int Tp = TB * 32;
+    const int t = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int f = 0; f < FV_FRAGS; ++f) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            const uint4 b = xl[(2 * f + g) * Tp + tb * 32 + t];
+            acc[tb] = Tr<EL>::mma(w[f], b, acc[tb]);
+        }
+    }
+}
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte register quad as a first-class value
+
+template <int N, int STRIDE>
+__device__ __forceinline__ void ld_vec(uint4 (&dst)[N], const uint4* __restrict__ src) {
+#pragma unroll
+    for (int v = 0; v < N; ++v) dst[v] = src[v * STRIDE];
+}
+template <int N, int STRIDE>
+__device__ __forceinline__ void ld_x(u32x4 (&dst)[N], const uint4* __restrict__ src) {
+#pragma unroll
+    for (int v = 0; v < N; ++v) dst[v] = *(const u32x4*)(src + v * STRIDE);
+}
+template <int N, int STRIDE>
+__device__ __forceinline__ void st_lds(uint4* dst, const u32x4 (&src)[N]) {
+#pragma unroll
+    for (int v = 0; v < N; ++v) *(u32x4*)(dst + v * STRIDE) = src[v];
+}
+template <int TB>
+__device__ __forceinline__ void zero_acc(floatx16 (&acc)[TB]) {
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[tb][i] = 0.f;
+}
+
+// Ends one segment (a run of K batches of one row group): either straight to the epilogue
+// (the segment covered the whole K range) or partials + ticket + last-arriver reduction.
+template <typename EL, int TB, int D, int EPI>
+__device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB], int gi, int seg_batches, int seg,
+                                           const float* rinv_lds, int* ticket_lds) {
+    constexpr int R = FV_R;
+    constexpr int Tp = TB * 32;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int strip = gi * R + wave;
+    if (seg_batches == a.NB) {
+        // the whole K range of this row group was ours: no partials, no ticket
+        if (strip < a.n_strips) {
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                float r[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) r[i] = acc[tb][i];
+                gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb, lane, r, rinv_lds);
+            }
+        }
+        return;
+    }
+    // Partials and tickets cross XCDs, whose L2s are not coherent with each other: the
+    // partials are written and read with agent-scope atomic accesses (write-through /
+    // cache-bypassing), so no whole-L2 write-back or invalidate is needed per wavefront.
+    // Layout [tb][16 registers][64 lanes]: every access of a wavefront is one 256-byte line.
+    float* pp = a.part + ((((size_t)blockIdx.x * a.segmax + seg) * R + wave) * TB) * 1024 + lane;
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            __hip_atomic_store(pp + tb * 1024 + i * 64, acc[tb][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // contributors of row group gi: workgroups c_first..c_last (each has a non-empty range)
+    const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
+    // Release without a whole-L2 write-back: the payload was stored with agent-scope atomic
+    // stores (write-through), so it is enough that every lane's stores have been acknowledged
+    // (vmcnt(0): on this target stores count in vmcnt) before the ticket is drawn.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt untouched
+    __syncthreads();
+    if (tid == 0)
+        *ticket_lds = __hip_atomic_fetch_add(&a.tickets[gi], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const bool last = (*ticket_lds == c_last - c_first);
+    if (last) {
+        // every other contributor's ticket, hence its acknowledged stores, precede ours; the
+        // partials are read with agent-scope atomic loads, which do not hit stale cache lines
+        if (tid == 0) __hip_atomic_store(&a.tickets[gi], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+        if (strip < a.n_strips) {
+#pragma unroll 1
+            for (int tb = 0; tb < TB; ++tb) {
+                float r[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) r[i] = 0.f;
+                // four contributions (64 loads) in flight at a time, summed in ascending order
+                for (int c0 = c_first; c0 <= c_last; c0 += 4) {
+                    float v[4][16];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int c = (c0 + k <= c_last) ? c0 + k : c_last;
+                        const int cseg = gi - a.tab_g0[c];
+                        const float* cp = a.part + ((((size_t)c * a.segmax + cseg) * R + wave) * TB + tb) * 1024 + lane;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            v[k][i] = __hip_atomic_load(cp + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float m = (c0 + k <= c_last) ? 1.f : 0.f;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) r[i] += m * v[k][i];
+                    }
+                }
+                gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb, lane, r, rinv_lds);
+            }
+        }
+    }
+    __syncthreads();   // ticket_lds is reused by the next segment
+}
+
+template <typename EL, int TB, int D, int EPI>
+__global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
+    extern __shared__ uint4 lds[];
+    constexpr int R = FV_R;
+    constexpr int Tp = TB * 32;
+    constexpr int CV = Tp * 16;          // uint4 per X chunk (Tp tokens x 256 B)
+    constexpr int XV = CV / (64 * R);    // uint4 per thread per chunk
+    static_assert(CV % (64 * R) == 0, "chunk must divide over the workgroup");
+    __shared__ float rinv_lds[Tp];
+    __shared__ __attribute__((aligned(16))) float red_lds[(EPI == EPI_RESID) ? 4 : 1024];
+    __shared__ int ticket_lds;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if ((int)blockIdx.x >= a.G) return;
+
+    // This workgroup's units [u0, u1) of the (row group, K batch) space, as ONE software-pipelined
+    // stream: the weight tiles of unit u+2 and the activation chunk of unit u+1 are in flight
+    // while unit u is multiplied, across row-group boundaries too.  Loads past the end of the
+    // range are clamped to the last unit (an L2 hit) instead of being branched around, so that
+    // the outstanding-load counts the waits are computed from stay exact.
+    const long long U = (long long)a.NG * a.NB;   // computed, not looked up: no extra round trip before the first load
+    const int u0 = (int)(U * blockIdx.x / a.G);
+    const int u1 = (int)(U * (blockIdx.x + 1) / a.G);
+    const uint4* __restrict__ wbase = a.Wt + (size_t)wave * a.NB * (FV_FRAGS * 64) + lane;
+    const size_t group_stride = (size_t)R * a.NB * (FV_FRAGS * 64);
+    const uint4* __restrict__ xbase = a.X + tid;
+    const int g0 = u0 / a.NB;
+
+    // prefetch position (row group, batch) kept incrementally; it stops at the last unit of the range
+    int pu = u0, pg = g0, pb = u0 - g0 * a.NB;
+    auto p_next = [&]() { if (pu + 1 < u1) { ++pu; if (++pb == a.NB) { pb = 0; ++pg; } } };
+    auto w_ptr = [&]() { return wbase + pg * group_stride + (size_t)pb * (FV_FRAGS * 64); };
+    auto x_ptr = [&]() { return xbase + (size_t)pb * CV; };
+
+    uint4 w[3][FV_FRAGS];
+    u32x4 xr[XV];
+    // prologue: W(u0) first, so that it is in flight during the statistics below
+    ld_vec<FV_FRAGS, 64>(w[0], w_ptr());
+    if constexpr (EPI != EPI_RESID) {
+        // RMSNorm factor of every token, while the first weight tiles are in flight.  The
+        // [n_ssq][Tp] partial sums of squares are read as float4 (4 tokens) with eight
+        // independent loads in flight per thread, then reduced over strip slices in LDS.
+        constexpr int C4 = Tp / 4;            // float4 columns
+        constexpr int SL = 256 / C4;          // strip slices
+        const int col = tid % C4, sl = tid / C4;
+        const float4* sp = (const float4*)a.ssq_in + col;
+        float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i0 = sl; i0 < a.n_ssq; i0 += 8 * SL) {
+            float4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int i = i0 + k * SL;
+                v[k] = (i < a.n_ssq) ? sp[(size_t)i * C4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { s4.x += v[k].x; s4.y += v[k].y; s4.z += v[k].z; s4.w += v[k].w; }
+        }
+        ((float4*)red_lds)[sl * C4 + col] = s4;
+        __syncthreads();
+        if (tid < Tp) {
+            float tot = 0.f;
+#pragma unroll
+            for (int p = 0; p < SL; ++p) tot += red_lds[p * Tp + tid];
+            rinv_lds[tid] = rsqrtf(tot * a.inv_h + a.eps);
+        }
+    }
+    // X(u0) -> LDS[0]; then X(u0+1) and W(u0+1) are issued in the same order as inside the loop
+    // (activation chunk before weight tiles), so the loop's wait counts hold from the first stage
+    ld_x<XV, 64 * R>(xr, x_ptr());
+    st_lds<XV, 64 * R>(lds + tid, xr);
+    __builtin_amdgcn_sched_barrier(0);
+    p_next();   // unit u0 + 1
+    ld_x<XV, 64 * R>(xr, x_ptr());
+    __builtin_amdgcn_sched_barrier(0);
+    ld_vec<FV_FRAGS, 64>(w[1], w_ptr());
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+
+    floatx16 acc[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[tb][i] = 0.f;
+    int seg = 0, seg_batches = 0;
+    int gi = g0, b = u0 - g0 * a.NB;
+
+    // one pipeline stage for unit u with weight register set S; the loads it issues go to set S2
+#define FV_STAGE(S, S2, u)                                                                              \
+    {                                                                                                   \
+        const int u_ = (u);                                                                             \
+        const int par_ = (u_ - u0) & 1;                                                                 \
+        if (u_ < u1) gemm_compute<EL, TB>(w[S], lds + par_ * CV, acc, lane);                            \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        st_lds<XV, 64 * R>(lds + (par_ ^ 1) * CV + tid, xr);                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        p_next(); /* unit u + 2 (or the last one) */                                                    \
+        ld_x<XV, 64 * R>(xr, x_ptr());                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        ld_vec<FV_FRAGS, 64>(w[S2], w_ptr());                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        __syncthreads();                                                                                \
+        if (u_ < u1) {                                                                                  \
+            ++seg_batches;                                                                              \
+            if (b == a.NB - 1 || u_ == u1 - 1) {                                                        \
+                gemm_flush<EL, TB, D, EPI>(a, acc, gi, seg_batches, seg, rinv_lds, &ticket_lds);        \
+                zero_acc<TB>(acc);                                                                      \
+                ++seg; seg_batches = 0; ++gi; b = 0;                                                    \
+            } else {                                                                                    \
+                ++b;                                                                                    \
+            }                                                                                           \
+        }                                                                                               \
+    }
+
+    for (int u = u0; u < u1; u += 3) {
+        FV_STAGE(0, 2, u)
+        FV_STAGE(1, 0, u + 1)
+        FV_STAGE(2, 1, u + 2)
+    }
+#undef FV_STAGE
+}
+
+#include "fv_gemm_direct.hpp"
 
 // ============================================================================ tree attention
 // For node t and query head qh: softmax over {cache slots 0..L-1} U {tree slots L+j : j in
