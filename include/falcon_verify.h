@@ -167,15 +167,23 @@ int fv_read_kv(fv_ctx* ctx, int32_t layer, int32_t slot0, int32_t n, float* k_ou
 enum { FV_ACT_X = 0, FV_ACT_XB = 1, FV_ACT_Q = 2, FV_ACT_ATTN = 3, FV_ACT_FFN = 4 };
 int fv_debug_read_activation(fv_ctx* ctx, int32_t which, int32_t n_nodes, float* out);
 
+/* Tuning aid: when the environment variable FV_PERSIST_TIMING is set, the persistent step kernel
+ * records, for layer 1, a 100 MHz time stamp before and after each of its grid barriers in every
+ * workgroup, and (second block) stamps from inside the GEMM phase whose number the variable
+ * holds (2 = O, 3 = gate/up, 4 = down); this copies both out as [2][256][16] (unused entries zero). */
+int fv_debug_persist_timing(fv_ctx* ctx, long long* out);
+
 /* ---- measurement ---- */
 
 /* When enabled, each subsequent step brackets its kernels with HIP events on the
  * context's stream and accumulates per-phase device time.  Off by default (the events
  * cost launch gaps). */
 int fv_set_profiling(fv_ctx* ctx, int32_t enabled);
-/* phases: the weight-streaming GEMM kernel; its fix-up/epilogue kernel; tree attention;
- * everything else (ingest, embedding, argmax, path scan, compaction) */
-enum { FV_PH_GEMM = 0, FV_PH_FIXUP = 1, FV_PH_ATTN = 2, FV_PH_OTHER = 3, FV_PH_COUNT = 4 };
+/* phases: the weight-streaming GEMM kernels; (unused, kept for layout); tree attention kernels;
+ * everything else (ingest, embedding, argmax, path scan, compaction); the persistent kernel that
+ * runs all decoder layers of a step of up to 64 nodes in one launch (then the GEMM phase holds
+ * only the LM head and the attention phase is empty) */
+enum { FV_PH_GEMM = 0, FV_PH_FIXUP = 1, FV_PH_ATTN = 2, FV_PH_OTHER = 3, FV_PH_PERSIST = 4, FV_PH_COUNT = 5 };
 /* Accumulated milliseconds and launch counts per phase since the last reset; reading
  * resets them.  Arrays of FV_PH_COUNT. */
 int fv_get_phase_times(fv_ctx* ctx, float* ms, int32_t* launches);

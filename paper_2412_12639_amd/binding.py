@@ -11,7 +11,7 @@ _LIB = None
 STATUS = {0: "FV_OK", -1: "FV_E_BAD_ARG", -2: "FV_E_TREE_ORDER", -3: "FV_E_TREE_DEPTH", -4: "FV_E_TOKEN_RANGE",
           -5: "FV_E_TREE_TOO_BIG", -6: "FV_E_CACHE_FULL", -7: "FV_E_ROOT_MISMATCH", -8: "FV_E_NO_PREFILL",
           -9: "FV_E_HIP"}
-PHASES = ("gemm", "fixup", "attn", "other")
+PHASES = ("gemm", "fixup", "attn", "other", "persistent")
 
 
 class FvError(RuntimeError):
@@ -262,10 +262,10 @@ class FalconVerifier:
         self._chk(self.lib.fv_set_profiling(self.ctx, 1 if on else 0), "fv_set_profiling")
 
     def phase_times(self):
-        ms = (C.c_float * 4)()
-        n = (C.c_int32 * 4)()
+        ms = (C.c_float * 5)()
+        n = (C.c_int32 * 5)()
         self._chk(self.lib.fv_get_phase_times(self.ctx, ms, n), "fv_get_phase_times")
-        return {PHASES[i]: (ms[i], n[i]) for i in range(4)}
+        return {PHASES[i]: (ms[i], n[i]) for i in range(5)}
 
     def last_step_ms(self) -> float:
         v = C.c_float()

@@ -47,6 +47,9 @@ struct Layout {
     size_t off_ssq = 0, off_rinv = 0, off_part = 0, part_bytes = 0, off_tickets = 0;
     size_t off_stepin = 0, off_mask = 0, off_pos = 0, off_rope = 0, off_am = 0, off_res = 0;
     size_t off_kvread = 0, off_stage = 0, stage_bytes = 0;
+    // persistent step kernel: rotating activation slots (one per layer + 1), barrier words, error flag
+    size_t off_rot = 0, rot_stride = 0, o_xa = 0, o_xm = 0, o_xba = 0, o_xbm = 0, o_ssqa = 0, o_ssqm = 0, o_q = 0, o_attn = 0, o_act = 0;
+    size_t off_bar = 0, off_err = 0, off_tstamp = 0, off_apart = 0, off_atick = 0;
     size_t total = 0;
 };
 
@@ -167,6 +170,28 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     for (size_t v : cands) if (v > st) st = v;
     L.stage_bytes = st * L.ESZ;
     L.off_stage = take(L.stage_bytes);
+    {   // slot of the persistent kernel, sized for 64 tokens
+        size_t r = 0;
+        auto sub = [&](size_t bytes) { size_t q = r; r = rup(r + bytes, 256); return q; };
+        const size_t T64 = 64;
+        L.o_xa = sub((size_t)c.hidden * T64 * 4);
+        L.o_xm = sub((size_t)c.hidden * T64 * 4);
+        L.o_xba = sub((size_t)L.gm[GM_QKV].Kpad * T64 * L.ESZ);
+        L.o_xbm = sub((size_t)L.gm[GM_QKV].Kpad * T64 * L.ESZ);
+        L.o_ssqa = sub((size_t)(c.hidden / 32) * T64 * 4);
+        L.o_ssqm = sub((size_t)(c.hidden / 32) * T64 * 4);
+        L.o_q = sub((size_t)qd * T64 * L.ESZ);
+        L.o_attn = sub((size_t)L.gm[GM_O].Kpad * T64 * L.ESZ);
+        L.o_act = sub((size_t)L.gm[GM_DN].Kpad * T64 * L.ESZ);
+        L.rot_stride = r;
+        L.off_rot = take(r * (c.n_layers + 1));
+        L.off_bar = take((64 + 32 * 256) * 4);
+        L.off_err = take(256);
+        L.off_tstamp = take(2 * 256 * 16 * 8);
+        // attention key-split partials: at most 8 parts per (head, node block) item, items for 256 rows
+        L.off_apart = take((size_t)c.n_q_heads * 8 * 8 * (d / 32 * 1024 + 64) * 4);
+        L.off_atick = take((size_t)c.n_q_heads * 8 * 4);
+    }
     L.total = o;
 }
 
@@ -203,12 +228,16 @@ struct fv_ctx {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     float last_ms = 0.f;
     bool profiling = false;
-    bool force_shared = false;   // FV_GEMM=shared: use the LDS-shared kernel for every token count (tuning)
+    bool force_shared = false;
+    bool persistent_ok = true;   // cooperative launch available and not switched off (FV_PERSISTENT=0)
+    bool last_persistent = false;
+    unsigned bar_gen = 0;
+    int* h_err = nullptr;        // pinned copy of the persistent kernel's error flag   // FV_GEMM=shared: use the LDS-shared kernel for every token count (tuning)
     std::vector<hipEvent_t> pev;       // event pool for profiling
     std::vector<int> pev_phase;        // phase of each (start, stop) pair
     size_t pev_used = 0;
-    float ph_ms[FV_PH_COUNT] = {0, 0, 0, 0};
-    int ph_n[FV_PH_COUNT] = {0, 0, 0, 0};
+    float ph_ms[FV_PH_COUNT] = {0, 0, 0, 0, 0};
+    int ph_n[FV_PH_COUNT] = {0, 0, 0, 0, 0};
 
     template <typename T> T* at(size_t off) const { return (T*)(arena + off); }
     char* layer_w(int l, int which) const { return arena + lay.off_layers + (size_t)l * lay.layer_w_bytes + lay.off_w[which]; }
@@ -244,7 +273,7 @@ int launch_gemm_t(fv_ctx* c, const GemmArgs& ga) {
 
 template <typename EL, int TB, int D, int EPI>
 int launch_gemm_direct_t(fv_ctx* c, const GemmArgs& ga) {
-    hipLaunchKernelGGL((k_gemm_direct<EL, TB, D, EPI>), dim3(ga.G), dim3(256), 0, c->stream, ga);
+    hipLaunchKernelGGL((k_gemm_direct<EL, TB, D, EPI>), dim3(ga.G), dim3(256), FV_DIRECT_SMEM_FLOATS(TB) * 4, c->stream, ga);
     return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
 }
 
@@ -265,6 +294,8 @@ int set_gemm_attrs_e() {
     // the 256-token instantiation double-buffers 2 x 64 KiB of activations in LDS
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 8, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 256 * 256));
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 4, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 256));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm_direct<EL, 1, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_DIRECT_SMEM_FLOATS(1) * 4));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm_direct<EL, 2, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_DIRECT_SMEM_FLOATS(2) * 4));
     return FV_OK;
 }
 template <typename EL, int D>
@@ -273,11 +304,67 @@ int set_gemm_attrs_d() {
     if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_RESID>();
     if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_SWIGLU>();
     if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_LOGITS>();
+    if (!rc) {
+        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 1, D>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(1, D) * 4));
+        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 2, D>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(2, D) * 4));
+    }
     return rc;
 }
 template <typename EL>
 int set_gemm_attrs(int head_dim) {
     return head_dim == 128 ? set_gemm_attrs_d<EL, 128>() : set_gemm_attrs_d<EL, 64>();
+}
+
+// Key split of the attention: enough workgroups per (head, node block) item to cover the CUs,
+// but at least two 32-key blocks each.
+int attn_key_split(int items, int n_keys, int n_wg) {
+    int ks = n_wg / (items > 0 ? items : 1);
+    const int nkb = (n_keys + 31) / 32;
+    if (ks > nkb / 2) ks = nkb / 2;
+    if (ks > 8) ks = 8;
+    if (ks < 1) ks = 1;
+    return ks;
+}
+
+// All decoder layers in one cooperative launch (see fv_step_persistent.hpp).  Returns FV_OK, or
+// a positive value if the launch was refused (the caller then takes the per-GEMM path).
+template <typename EL, int D>
+int launch_persistent(fv_ctx* c, int T, int Tp, int L) {
+    const fv_cfg& cf = c->cfg;
+    const Layout& ly = c->lay;
+    PersistArgs pa;
+    memset(&pa, 0, sizeof(pa));
+    pa.n_layers = cf.n_layers; pa.T = T; pa.Tp = Tp; pa.L = L; pa.h = cf.hidden; pa.Hq = cf.n_q_heads; pa.Hkv = cf.n_kv_heads;
+    pa.S_pad = ly.S_pad; pa.n_ssq = cf.hidden / 32; pa.inv_h = 1.f / (float)cf.hidden; pa.eps = cf.rms_eps;
+    pa.scale = 1.f / std::sqrt((float)D);
+    pa.w_layers = c->arena + ly.off_layers; pa.layer_w_bytes = ly.layer_w_bytes;
+    for (int i = 0; i < 4; ++i) pa.off_w[i] = ly.off_w[i];
+    pa.kc = c->arena + ly.off_k; pa.vc = c->arena + ly.off_v; pa.kv_layer_bytes = ly.kv_layer_bytes;
+    pa.gains = c->at<float>(ly.off_gains); pa.rope_cs = c->at<float2>(ly.off_rope); pa.mask = c->at<uint64_t>(ly.off_mask);
+    pa.rot = c->arena + ly.off_rot; pa.rot_stride = ly.rot_stride;
+    pa.o_xa = ly.o_xa; pa.o_xm = ly.o_xm; pa.o_xba = ly.o_xba; pa.o_xbm = ly.o_xbm; pa.o_ssqa = ly.o_ssqa; pa.o_ssqm = ly.o_ssqm;
+    pa.o_q = ly.o_q; pa.o_attn = ly.o_attn; pa.o_act = ly.o_act;
+    pa.part = c->at<float>(ly.off_part); pa.tickets = c->at<int>(ly.off_tickets);
+    pa.attn_part = c->at<float>(ly.off_apart); pa.attn_tickets = c->at<int>(ly.off_atick);
+    pa.attn_ks = attn_key_split(cf.n_q_heads * (Tp / 32), L + T, 256);
+    pa.bar = c->at<unsigned>(ly.off_bar); pa.gen0 = c->bar_gen; pa.err = c->at<int>(ly.off_err);
+    pa.tstamp = getenv("FV_PERSIST_TIMING") ? c->at<long long>(ly.off_tstamp) : nullptr;
+    pa.ts_phase = getenv("FV_PERSIST_TIMING") ? atoi(getenv("FV_PERSIST_TIMING")) : 0;
+    int grid = 1;
+    for (int i = 0; i < 4; ++i) {
+        const GemmPlan& p = ly.gd[i];
+        pa.g[i].NG = p.NG; pa.g[i].NB = p.NB; pa.g[i].G = p.G; pa.g[i].segmax = p.segmax; pa.g[i].n_strips = p.n_strips;
+        pa.g[i].tab = c->at<int>(p.off_tab);
+        if (p.G > grid) grid = p.G;
+    }
+    if (grid > 256) return 1;   // the barrier polls one slot per thread of workgroup 0
+    void* args[] = {&pa};
+    const void* fn = (Tp == 32) ? (const void*)k_step_persistent<EL, 1, D> : (const void*)k_step_persistent<EL, 2, D>;
+    const unsigned smem = (Tp == 32 ? FV_PERSIST_SMEM_FLOATS(1, D) : FV_PERSIST_SMEM_FLOATS(2, D)) * 4;
+    hipError_t e = hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), args, smem, c->stream);
+    if (e != hipSuccess) { (void)hipGetLastError(); return 1; }
+    c->bar_gen += 5u * (unsigned)cf.n_layers - 1u;
+    return FV_OK;
 }
 
 enum StepMode { STEP_VERIFY = 0, STEP_PREFILL_MID = 1, STEP_PREFILL_LAST = 2 };
@@ -293,6 +380,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
     hipStream_t st = c->stream;
     c->pev_used = 0;
 
+    bool persistent = c->persistent_ok && Tp <= 64;
     HIPCHK(hipMemcpyAsync(c->at<int32_t>(ly.off_stepin), c->h_in, 3 * FV_MAX_TREE * 4, hipMemcpyHostToDevice, st));
     HIPCHK(hipEventRecord(c->ev0, st));
     {
@@ -304,7 +392,10 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         hipLaunchKernelGGL(k_ingest, dim3(1), dim3(256), 0, st, ia);
         EmbedArgs ea;
         ea.table = c->at<void>(ly.off_embed); ea.tok = c->at<int32_t>(ly.off_stepin); ea.gain = c->gain(0);
-        ea.x = c->at<float>(ly.off_x); ea.xb = c->at<void>(ly.off_xb); ea.ssq_part = c->at<float>(ly.off_ssq);
+        // the persistent kernel reads layer 0's slot of its rotating buffers
+        ea.x = persistent ? (float*)(c->arena + ly.off_rot + ly.o_xa) : c->at<float>(ly.off_x);
+        ea.xb = persistent ? (void*)(c->arena + ly.off_rot + ly.o_xba) : c->at<void>(ly.off_xb);
+        ea.ssq_part = persistent ? (float*)(c->arena + ly.off_rot + ly.o_ssqa) : c->at<float>(ly.off_ssq);
         ea.h = h; ea.T = T; ea.Tp = Tp;
         hipLaunchKernelGGL((k_embed<EL>), dim3(h / 32), dim3(Tp < 64 ? 64 : Tp), 0, st, ea);
     }
@@ -324,7 +415,23 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         return ga;
     };
 
-    for (int l = 0; l < cf.n_layers; ++l) {
+    if (persistent) {
+        PhaseTimer pt(c, FV_PH_PERSIST);
+        const int rc = launch_persistent<EL, D>(c, T, Tp, L);
+        if (rc < 0) return rc;
+        if (rc > 0) {   // launch refused: this context takes the per-GEMM path from now on (the embedding is redone below)
+            c->persistent_ok = false;
+            persistent = false;
+            EmbedArgs ea;
+            ea.table = c->at<void>(ly.off_embed); ea.tok = c->at<int32_t>(ly.off_stepin); ea.gain = c->gain(0);
+            ea.x = c->at<float>(ly.off_x); ea.xb = c->at<void>(ly.off_xb); ea.ssq_part = c->at<float>(ly.off_ssq);
+            ea.h = h; ea.T = T; ea.Tp = Tp;
+            hipLaunchKernelGGL((k_embed<EL>), dim3(h / 32), dim3(Tp < 64 ? 64 : Tp), 0, st, ea);
+            HIPCHK(hipGetLastError());
+        }
+    }
+    const size_t last_slot = ly.off_rot + (size_t)cf.n_layers * ly.rot_stride;
+    for (int l = 0; l < cf.n_layers && !persistent; ++l) {
         int rc;
         {   // q, k, v projections of the normalised input, rotary at pos = L + depth, K/V to cache slots L + i
             PhaseTimer pt(c, FV_PH_GEMM);
@@ -341,13 +448,15 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             aa.out = c->at<void>(ly.off_attn); aa.mask = c->at<uint64_t>(ly.off_mask);
             aa.Tp = Tp; aa.T = T; aa.L = L; aa.Hq = cf.n_q_heads; aa.Hkv = cf.n_kv_heads; aa.S_pad = ly.S_pad;
             aa.scale = 1.f / std::sqrt((float)D);
-            hipLaunchKernelGGL((k_attn<EL, D>), dim3(cf.n_q_heads * (Tp / 32)), dim3(256), 0, st, aa);
+            aa.ks = attn_key_split(cf.n_q_heads * (Tp / 32), L + T, 256);
+            aa.part = c->at<float>(ly.off_apart); aa.tickets = c->at<int>(ly.off_atick);
+            hipLaunchKernelGGL((k_attn<EL, D>), dim3(cf.n_q_heads * (Tp / 32) * aa.ks), dim3(256), 0, st, aa);
             HIPCHK(hipGetLastError());
         }
         {   // output projection, residual add, statistics + input of the FFN norm
             PhaseTimer pt(c, FV_PH_GEMM);
             GemmArgs ga = gemm_args(GM_O, c->layer_w(l, 1), ly.off_attn);
-            ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb); ga.gain_next = c->gain(2 * l + 1);
+            ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb); ga.gain_next = c->gain(2 * l + 1);
             ga.ssq_out = c->at<float>(ly.off_ssq);
             rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, direct);
             if (rc) return rc;
@@ -362,7 +471,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         {   // down projection, residual add, statistics + input of the next norm
             PhaseTimer pt(c, FV_PH_GEMM);
             GemmArgs ga = gemm_args(GM_DN, c->layer_w(l, 3), ly.off_act);
-            ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb);
+            ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb);
             ga.gain_next = (l + 1 < cf.n_layers) ? c->gain(2 * (l + 1)) : c->gain(2 * cf.n_layers);
             ga.ssq_out = c->at<float>(ly.off_ssq);
             rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, direct);
@@ -373,7 +482,8 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
     if (mode != STEP_PREFILL_MID) {
         {
             PhaseTimer pt(c, FV_PH_GEMM);
-            GemmArgs ga = gemm_args(GM_LM, c->at<void>(ly.off_lm), ly.off_xb);
+            GemmArgs ga = gemm_args(GM_LM, c->at<void>(ly.off_lm), persistent ? last_slot + ly.o_xba : ly.off_xb);
+            if (persistent) ga.ssq_in = (const float*)(c->arena + last_slot + ly.o_ssqa);
             ga.logits = c->at<float>(ly.off_logits); ga.Vpad = ly.Vpad;
             int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, direct);
             if (rc) return rc;
@@ -399,7 +509,10 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         HIPCHK(hipMemcpyAsync(c->h_res, c->at<FvResult>(ly.off_res), sizeof(FvResult), hipMemcpyDeviceToHost, st));
     else if (mode == STEP_PREFILL_LAST)
         HIPCHK(hipMemcpyAsync(&c->h_res->next_token, c->at<int32_t>(ly.off_am) + (T - 1), 4, hipMemcpyDeviceToHost, st));
+    if (persistent) HIPCHK(hipMemcpyAsync(c->h_err, c->at<int>(ly.off_err), 4, hipMemcpyDeviceToHost, st));
     HIPCHK(hipStreamSynchronize(st));
+    if (persistent && *c->h_err) return FV_E_HIP;   // a grid-barrier wait gave up: results are not valid
+    c->last_persistent = persistent;
     HIPCHK(hipEventElapsedTime(&c->last_ms, c->ev0, c->ev1));
     if (c->profiling) {
         for (size_t i = 0; i + 1 < c->pev_used; i += 2) {
@@ -552,9 +665,17 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     c->arena = (char*)dev_arena;
     c->stream = (hipStream_t)hip_stream;
     { const char* e = getenv("FV_GEMM"); c->force_shared = e && !strcmp(e, "shared"); }
+    { const char* e = getenv("FV_PERSISTENT"); if (e && !strcmp(e, "0")) c->persistent_ok = false; }
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipHostMalloc((void**)&c->h_res, sizeof(FvResult), hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
+    if (hipHostMalloc((void**)&c->h_err, 64, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
+    *c->h_err = 0;
+    {
+        int dev = 0, coop = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop)
+            c->persistent_ok = false;
+    }
     if (hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) return fail(FV_E_HIP);
     // zero everything except the weights (they are written by fv_init_weights): pad lanes of
     // activations and never-written cache slots must hold finite values
@@ -577,6 +698,7 @@ void fv_destroy(fv_ctx* c) {
     if (!c) return;
     if (c->h_in) (void)hipHostFree(c->h_in);
     if (c->h_res) (void)hipHostFree(c->h_res);
+    if (c->h_err) (void)hipHostFree(c->h_err);
     if (c->ev0) (void)hipEventDestroy(c->ev0);
     if (c->ev1) (void)hipEventDestroy(c->ev1);
     for (hipEvent_t e : c->pev) (void)hipEventDestroy(e);
@@ -706,12 +828,14 @@ int fv_debug_read_activation(fv_ctx* c, int32_t which, int32_t n, float* out) {
     size_t off;
     int F;
     bool f32 = (cf.dtype == FV_F32);
+    const bool pe = c->last_persistent;   // the persistent kernel keeps one slot of buffers per layer
+    const size_t sl_last = ly.off_rot + (size_t)cf.n_layers * ly.rot_stride, sl_prev = sl_last - ly.rot_stride;
     switch (which) {
-        case FV_ACT_X: off = ly.off_x; F = cf.hidden; f32 = true; break;
-        case FV_ACT_XB: off = ly.off_xb; F = cf.hidden; break;
-        case FV_ACT_Q: off = ly.off_q; F = qd; break;
-        case FV_ACT_ATTN: off = ly.off_attn; F = qd; break;
-        case FV_ACT_FFN: off = ly.off_act; F = cf.ffn; break;
+        case FV_ACT_X: off = pe ? sl_last + ly.o_xa : ly.off_x; F = cf.hidden; f32 = true; break;
+        case FV_ACT_XB: off = pe ? sl_last + ly.o_xba : ly.off_xb; F = cf.hidden; break;
+        case FV_ACT_Q: off = pe ? sl_prev + ly.o_q : ly.off_q; F = qd; break;
+        case FV_ACT_ATTN: off = pe ? sl_prev + ly.o_attn : ly.off_attn; F = qd; break;
+        case FV_ACT_FFN: off = pe ? sl_prev + ly.o_act : ly.off_act; F = cf.ffn; break;
         default: return FV_E_BAD_ARG;
     }
     const int E = f32 ? 4 : 8, esz = f32 ? 4 : 2;
@@ -725,6 +849,12 @@ int fv_debug_read_activation(fv_ctx* c, int32_t which, int32_t n, float* out) {
             else { uint32_t u = (uint32_t)((const uint16_t*)buf.data())[i] << 16; memcpy(&v, &u, 4); }
             out[(size_t)t * F + f] = v;
         }
+    return FV_OK;
+}
+
+int fv_debug_persist_timing(fv_ctx* c, long long* out) {
+    if (!c || !out) return FV_E_BAD_ARG;
+    HIPCHK(hipMemcpy(out, c->at<long long>(c->lay.off_tstamp), 2 * 256 * 16 * 8, hipMemcpyDeviceToHost));
     return FV_OK;
 }
 

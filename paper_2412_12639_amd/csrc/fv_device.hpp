@@ -76,23 +76,44 @@ template <> struct Tr<F32> {
     }
 };
 
+// ---- stores that other workgroups of the SAME kernel launch will read (persistent step kernel).
+// The XCDs' L2 caches are not coherent with each other inside a launch, so such data is written
+// with agent-scope atomic stores, which the hardware performs write-through (sc1).  COH = false
+// gives plain stores for data that is only read by later launches.
+template <bool COH> __device__ __forceinline__ void st_u64(void* p, uint64_t v) {
+    if constexpr (COH) __hip_atomic_store((uint64_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *(uint64_t*)p = v;
+}
+template <bool COH> __device__ __forceinline__ void st_f32(float* p, float v) {
+    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool COH> __device__ __forceinline__ void st_f4(float4* p, float4 v) {
+    if constexpr (COH) {
+        st_u64<true>(p, (uint64_t)__builtin_bit_cast(uint32_t, v.x) | ((uint64_t)__builtin_bit_cast(uint32_t, v.y) << 32));
+        st_u64<true>((char*)p + 8, (uint64_t)__builtin_bit_cast(uint32_t, v.z) | ((uint64_t)__builtin_bit_cast(uint32_t, v.w) << 32));
+    } else *p = v;
+}
+// one cache element (bf16 or fp32)
+template <typename EL, bool COH> __device__ __forceinline__ void st_elem(void* p, size_t i, float v);
+template <> __device__ __forceinline__ void st_elem<BF16, false>(void* p, size_t i, float v) { Tr<BF16>::store(p, i, v); }
+template <> __device__ __forceinline__ void st_elem<F32, false>(void* p, size_t i, float v) { Tr<F32>::store(p, i, v); }
+template <> __device__ __forceinline__ void st_elem<BF16, true>(void* p, size_t i, float v) {
+    __bf16 h = (__bf16)v;
+    __hip_atomic_store((uint16_t*)p + i, __builtin_bit_cast(uint16_t, h), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <> __device__ __forceinline__ void st_elem<F32, true>(void* p, size_t i, float v) { st_f32<true>((float*)p + i, v); }
+
 // Store four consecutive features f0..f0+3 (f0 % 4 == 0) of token t into a vector-major
 // activation buffer.
-template <typename EL>
-__device__ __forceinline__ void store4_act(void* base, int Tp, int f0, int t, float a, float b, float c, float d);
-
-template <>
-__device__ __forceinline__ void store4_act<BF16>(void* base, int Tp, int f0, int t, float a, float b, float c, float d) {
-    char* p = (char*)base + ((size_t)(f0 >> 3) * Tp + t) * 16 + (f0 & 7) * 2;
-    uint2 v;
-    v.x = pack_bf16x2(a, b);
-    v.y = pack_bf16x2(c, d);
-    *(uint2*)p = v;
-}
-template <>
-__device__ __forceinline__ void store4_act<F32>(void* base, int Tp, int f0, int t, float a, float b, float c, float d) {
-    float4* p = (float4*)base + ((size_t)(f0 >> 2) * Tp + t);
-    *p = make_float4(a, b, c, d);
+template <typename EL, bool COH = false>
+__device__ __forceinline__ void store4_act(void* base, int Tp, int f0, int t, float a, float b, float c, float d) {
+    if constexpr (Tr<EL>::E == 8) {
+        char* p = (char*)base + ((size_t)(f0 >> 3) * Tp + t) * 16 + (f0 & 7) * 2;
+        st_u64<COH>(p, (uint64_t)pack_bf16x2(a, b) | ((uint64_t)pack_bf16x2(c, d) << 32));
+    } else {
+        st_f4<COH>((float4*)base + ((size_t)(f0 >> 2) * Tp + t), make_float4(a, b, c, d));
+    }
 }
 
 // Element index of (position pos, feature f) inside one (layer, kv-head) K slab:

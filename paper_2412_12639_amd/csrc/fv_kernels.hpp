@@ -110,6 +110,8 @@ struct GemmArgs {
     // first row group, and the first / last contributing workgroup of every row group
     const int* tab_u0; const int* tab_g0; const int* tab_cf; const int* tab_cl;
     int T, n_strips;     // real tokens; strips that carry real rows
+    int epi;             // epilogue, for bodies that choose it at run time
+    long long* ts;       // optional time stamps (tuning), else null
     // RMSNorm statistics of the input (QKV, SWIGLU, LOGITS): rinv[t] = rsqrt(sum_s ssq_in[s][t] / h + eps)
     const float* ssq_in; // [n_ssq][Tp]
     int n_ssq;
@@ -120,7 +122,8 @@ struct GemmArgs {
     void* vcache;
     const float2* rope_cs;   // [Tp][D/2]
     int Hq, Hkv, L, S_pad;
-    // EPI_RESID: x += y; xb = x * gain_next; partial sums of squares of the new x
+    // EPI_RESID: x = x_in + y (x_in may be x); xb = x * gain_next; partial sums of squares of the new x
+    const float* x_in;
     float* x;
     void* xb;
     const float* gain_next;
@@ -134,7 +137,7 @@ struct GemmArgs {
 
 // Epilogue of one 32-row strip x 32-token block, in accumulator layout: lane (tl, g), acc[i] is
 // row 8*(i/4) + 4*g + i%4 of the strip for token tb*32 + tl.
-template <typename EL, int D, int EPI>
+template <typename EL, int D, int EPI, bool COH = false>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
                                               const float* rinv_lds) {
     const int tl = lane & 31, g = lane >> 5;
@@ -144,16 +147,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk) {
             const int f0 = strip * 32 + 8 * blk + 4 * g;
-            float4* xp = (float4*)a.x + (size_t)(f0 >> 2) * Tp + t;
-            float4 xv = *xp;
+            float4 xv = ((const float4*)a.x_in)[(size_t)(f0 >> 2) * Tp + t];
             xv.x += acc[4 * blk]; xv.y += acc[4 * blk + 1]; xv.z += acc[4 * blk + 2]; xv.w += acc[4 * blk + 3];
-            *xp = xv;
-            store4_act<EL>(a.xb, Tp, f0, t, xv.x * a.gain_next[f0], xv.y * a.gain_next[f0 + 1],
+            st_f4<COH>((float4*)a.x + (size_t)(f0 >> 2) * Tp + t, xv);
+            store4_act<EL, COH>(a.xb, Tp, f0, t, xv.x * a.gain_next[f0], xv.y * a.gain_next[f0 + 1],
                            xv.z * a.gain_next[f0 + 2], xv.w * a.gain_next[f0 + 3]);
             ssq += xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
         }
         ssq += __shfl_xor(ssq, 32);
-        if (g == 0) a.ssq_out[(size_t)strip * Tp + t] = ssq;
+        if (g == 0) st_f32<COH>(a.ssq_out + (size_t)strip * Tp + t, ssq);
     } else {
         const float rs = rinv_lds[t];
 #pragma unroll
@@ -162,8 +164,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
             for (int blk = 0; blk < 4; ++blk) {
                 const int f0 = strip * 32 + 8 * blk + 4 * g;
-                *(float4*)(a.logits + (size_t)t * a.Vpad + f0) =
-                    make_float4(acc[4 * blk], acc[4 * blk + 1], acc[4 * blk + 2], acc[4 * blk + 3]);
+                st_f4<COH>((float4*)(a.logits + (size_t)t * a.Vpad + f0),
+                           make_float4(acc[4 * blk], acc[4 * blk + 1], acc[4 * blk + 2], acc[4 * blk + 3]));
             }
         } else if constexpr (EPI == EPI_SWIGLU) {
             // strip covers activation features [16*strip, 16*strip+16): accumulator blocks 0,2 are
@@ -176,7 +178,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
                     const float gt = acc[8 * pr + c], up = acc[8 * pr + 4 + c];
                     o[c] = gt / (1.f + __expf(-gt)) * up;
                 }
-                store4_act<EL>(a.act, Tp, 16 * strip + 8 * pr + 4 * g, t, o[0], o[1], o[2], o[3]);
+                store4_act<EL, COH>(a.act, Tp, 16 * strip + 8 * pr + 4 * g, t, o[0], o[1], o[2], o[3]);
             }
         } else {  // EPI_QKV
             constexpr int SPH = D / 32;   // strips per head
@@ -198,8 +200,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
                     for (int pr = 0; pr < 2; ++pr) {
                         const int f1 = head * D + 16 * j + 8 * pr + 4 * g;
-                        store4_act<EL>(a.q_out, Tp, f1, t, lo_v[pr][0], lo_v[pr][1], lo_v[pr][2], lo_v[pr][3]);
-                        store4_act<EL>(a.q_out, Tp, f1 + D / 2, t, hi_v[pr][0], hi_v[pr][1], hi_v[pr][2], hi_v[pr][3]);
+                        store4_act<EL, COH>(a.q_out, Tp, f1, t, lo_v[pr][0], lo_v[pr][1], lo_v[pr][2], lo_v[pr][3]);
+                        store4_act<EL, COH>(a.q_out, Tp, f1 + D / 2, t, hi_v[pr][0], hi_v[pr][1], hi_v[pr][2], hi_v[pr][3]);
                     }
                 } else if (t < a.T) {
                     const int kh = head - a.Hq;
@@ -210,8 +212,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
                             const int f1 = 16 * j + 8 * pr + 4 * g + c;
-                            Tr<EL>::store(slab, kcache_index<EL, D>(pos, f1), lo_v[pr][c]);
-                            Tr<EL>::store(slab, kcache_index<EL, D>(pos, f1 + D / 2), hi_v[pr][c]);
+                            st_elem<EL, COH>(slab, kcache_index<EL, D>(pos, f1), lo_v[pr][c]);
+                            st_elem<EL, COH>(slab, kcache_index<EL, D>(pos, f1 + D / 2), hi_v[pr][c]);
                         }
                 }
             } else if (t < a.T) {
@@ -221,7 +223,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int f = 32 * j + 8 * (i >> 2) + 4 * g + (i & 3);
-                    Tr<EL>::store(slab, vcache_index<EL, D>(pos, f), acc[i]);
+                    st_elem<EL, COH>(slab, vcache_index<EL, D>(pos, f), acc[i]);
                 }
             }
         }
@@ -484,19 +486,29 @@ struct AttnArgs {
     const uint64_t* mask;    // [Tp][4]
     int Tp, T, L, Hq, Hkv, S_pad;
     float scale;
+    // key split: every (head, node block) item is shared by `ks` workgroups, each taking a
+    // contiguous run of 32-key blocks; their (max, sum, unnormalised output) triples meet in
+    // `part` ([item*ks + k][D/32 * 1024 + 64] floats) behind one ticket per item
+    int ks;
+    float* part;
+    int* tickets;
 };
 
-template <typename EL, int D>
-__global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
+#define FV_ATTN_SMEM_FLOATS(D) (3 * ((D) / 32) * 64 * 16 + 8 * 32 + 4)
+#define FV_ATTN_PART_FLOATS(D) (((D) / 32) * 1024 + 64)
+
+// One (query head, block of 32 nodes) item, key part `part` of a.ks.  COH: the output is read by
+// other workgroups of the same launch.
+template <typename EL, int D, bool COH>
+__device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part, float* smem) {
     constexpr int E = Tr<EL>::E;
     constexpr int NF = D / (2 * E);      // K frags per key block
     constexpr int NQ = 32 / (2 * E);     // V frags per (key block, 32 features)
     constexpr int DB = D / 32;
-    __shared__ float smem[3 * DB * 64 * 16 + 8 * 32];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int tl = lane & 31, g = lane >> 5;
     const int TB = a.Tp >> 5;
-    const int qh = blockIdx.x / TB, tb = blockIdx.x % TB;
+    const int qh = item / TB, tb = item % TB;
     const int kh = qh / (a.Hq / a.Hkv);
     const int t = tb * 32 + tl;
 
@@ -520,8 +532,9 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 
     const int n_keys = a.L + a.T;
     const int nkb = (n_keys + 31) >> 5;
+    const int kb_lo = nkb * part / a.ks, kb_hi = nkb * (part + 1) / a.ks;   // this workgroup's key blocks
     const int lidx = tl * 2 + g;   // position of this lane's 16 bytes inside a 1 KiB tile
-    for (int kb = wave; kb < nkb; kb += 4) {
+    for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
         floatx16 s;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[i] = 0.f;
@@ -582,32 +595,97 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     }
     if (g == 0) { sm[wave * 32 + tl] = m_run; sl[wave * 32 + tl] = l_run; }
     __syncthreads();
-    if (wave != 0) return;
-    float M = -1e30f;
+    int* ticket_lds = (int*)(sl + 4 * 32);
+    float M = -1e30f, lsum = 0.f;
+    float r[DB][16];
+    if (wave == 0) {
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, sm[w * 32 + tl]);
-    float wgt[4], lsum = 0.f;
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, sm[w * 32 + tl]);
+        float wgt[4];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) { wgt[w] = __expf(sm[w * 32 + tl] - M); lsum += wgt[w] * sl[w * 32 + tl]; }
-    const float inv = (lsum > 0.f) ? 1.f / lsum : 0.f;
+        for (int w = 0; w < 4; ++w) { wgt[w] = __expf(sm[w * 32 + tl] - M); lsum += wgt[w] * sl[w * 32 + tl]; }
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-        float r[16];
+        for (int db = 0; db < DB; ++db) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) r[i] = wgt[0] * o[db][i];
+            for (int i = 0; i < 16; ++i) r[db][i] = wgt[0] * o[db][i];
 #pragma unroll
-        for (int w = 1; w < 4; ++w)
+            for (int w = 1; w < 4; ++w)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = ((const float4*)so)[(((w - 1) * DB + db) * 64 + lane) * 4 + q];
-                r[4 * q] += wgt[w] * v.x; r[4 * q + 1] += wgt[w] * v.y; r[4 * q + 2] += wgt[w] * v.z; r[4 * q + 3] += wgt[w] * v.w;
-            }
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = ((const float4*)so)[(((w - 1) * DB + db) * 64 + lane) * 4 + q];
+                    r[db][4 * q] += wgt[w] * v.x; r[db][4 * q + 1] += wgt[w] * v.y;
+                    r[db][4 * q + 2] += wgt[w] * v.z; r[db][4 * q + 3] += wgt[w] * v.w;
+                }
+        }
+    }
+    if (a.ks == 1) {
+        if (wave == 0) {
+            const float inv = (lsum > 0.f) ? 1.f / lsum : 0.f;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int blk = 0; blk < 4; ++blk)
+                    store4_act<EL, COH>(a.out, a.Tp, qh * D + db * 32 + 8 * blk + 4 * g, t, r[db][4 * blk] * inv,
+                                        r[db][4 * blk + 1] * inv, r[db][4 * blk + 2] * inv, r[db][4 * blk + 3] * inv);
+        }
+        return;
+    }
+    // ---- several workgroups share this item: partial triple out (agent-scope atomic stores,
+    // acknowledged), ticket, and the last arriver combines all parts in part order
+    constexpr int PF = FV_ATTN_PART_FLOATS(D);
+    if (wave == 0) {
+        float* pp = a.part + (size_t)(item * a.ks + part) * PF + lane;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) __hip_atomic_store(pp + (db * 16 + i) * 64, r[db][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (g == 0) {
+            __hip_atomic_store(pp + DB * 1024, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);         // lanes 0..31
+            __hip_atomic_store(pp + DB * 1024 + 32, lsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        if (lane == 0) *ticket_lds = __hip_atomic_fetch_add(&a.tickets[item], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (*ticket_lds != a.ks - 1) return;
+    if (tid == 0) __hip_atomic_store(&a.tickets[item], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next use
+    // wavefront w combines 32-feature block w (blocks beyond D/32 have no wavefront)
+    const float* base = a.part + (size_t)item * a.ks * PF;
+    float Mx = -1e30f;
+    for (int c = 0; c < a.ks; ++c)
+        Mx = fmaxf(Mx, __hip_atomic_load(base + (size_t)c * PF + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    for (int db = wave; db < DB; db += 4) {
+        float accv[16], ltot = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) accv[i] = 0.f;
+        for (int c = 0; c < a.ks; ++c) {
+            const float* cp = base + (size_t)c * PF;
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = __hip_atomic_load(cp + (db * 16 + i) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float mc = __hip_atomic_load(cp + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float lc = __hip_atomic_load(cp + DB * 1024 + 32 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float wc = __expf(mc - Mx);
+            ltot += wc * lc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) accv[i] += wc * v[i];
+        }
+        const float inv = (ltot > 0.f) ? 1.f / ltot : 0.f;
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk)
-            store4_act<EL>(a.out, a.Tp, qh * D + db * 32 + 8 * blk + 4 * g, t, r[4 * blk] * inv, r[4 * blk + 1] * inv,
-                           r[4 * blk + 2] * inv, r[4 * blk + 3] * inv);
+            store4_act<EL, COH>(a.out, a.Tp, qh * D + db * 32 + 8 * blk + 4 * g, t, accv[4 * blk] * inv, accv[4 * blk + 1] * inv,
+                                accv[4 * blk + 2] * inv, accv[4 * blk + 3] * inv);
     }
 }
+
+// grid = items * ks
+template <typename EL, int D>
+__global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
+    __shared__ __attribute__((aligned(16))) float smem[FV_ATTN_SMEM_FLOATS(D)];
+    attn_body<EL, D, false>(a, blockIdx.x / a.ks, blockIdx.x % a.ks, smem);
+}
+
+#include "fv_step_persistent.hpp"
 
 // ============================================================================ argmax
 // Greedy choice per node: wavefront shuffle reduction on (value, index), lowest index on ties.

@@ -255,3 +255,26 @@ def test_rejected_calls_change_nothing(fvmod):
     a, acc, nxt = g.verify_tree([root, 1, 2], [-1, 0, 1], [0, 1, 2])
     assert 0 <= a <= 2
     g.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "small-gqa"])
+def test_persistent_kernel_and_per_gemm_path_agree(fvmod, name, monkeypatch):
+    """Steps of up to 64 nodes run all layers in one persistent kernel by default; FV_PERSISTENT=0
+    takes one launch per GEMM.  Both must match the oracle, and each other bit for bit (same
+    split, same summation order)."""
+    s, w = SHAPES[name], weights_of(name)
+    tol = H.tol_for(s)
+    say("persistent-vs-launches", name)
+    case = H.planted_case(s, w, 70, 48, [6, 3, 2, 2, 1, 1], 3, seed=2)
+    outs = []
+    for flag in ("1", "0"):
+        monkeypatch.setenv("FV_PERSISTENT", flag)
+        g = make_gpu(fvmod, s, w, max_seq=160, max_tree=64)
+        assert g.prefill(case["prefix"]) == case["root"]
+        got = g.verify_tree(case["tokens"], case["parent"], case["depth"])
+        e = H.check_step(g, case, got, tol)
+        say("FV_PERSISTENT=" + flag, "err", e, "step ms", g.last_step_ms())
+        outs.append(g.logits(48).copy())
+        H.check_cache(g, case["oracle"], s, 70 + got[0] + 1, tol)
+        g.close()
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
