@@ -6,8 +6,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libfalcon_verify.so")
 SRC = os.path.join(HERE, "csrc", "falcon_verify.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "fv_kernels.hpp"), os.path.join(HERE, "csrc", "fv_device.hpp"),
-        os.path.join(os.path.dirname(HERE), "include", "falcon_verify.h")]
+DEPS = sorted(os.path.join(HERE, "csrc", f) for f in os.listdir(os.path.join(HERE, "csrc"))) + \
+    [os.path.join(os.path.dirname(HERE), "include", "falcon_verify.h")]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -18,7 +18,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument", "-o", LIB, SRC]
     if verbose:
-        cmd.insert(1, "-save-temps=obj")
+        print(" ".join(cmd), file=sys.stderr)
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -228,7 +228,7 @@ struct fv_ctx {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     float last_ms = 0.f;
     bool profiling = false;
-    bool force_shared = false;
+    int gemm_kind = 1;        // GemmKind used up to 64 tokens
     bool persistent_ok = true;   // cooperative launch available and not switched off (FV_PERSISTENT=0)
     bool last_persistent = false;
     unsigned bar_gen = 0;
@@ -277,9 +277,19 @@ int launch_gemm_direct_t(fv_ctx* c, const GemmArgs& ga) {
     return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
 }
 
+template <typename EL, int TB, int D, int EPI>
+int launch_gemm_wide_t(fv_ctx* c, const GemmArgs& ga) {
+    hipLaunchKernelGGL((k_gemm_wide<EL, TB, D, EPI>), dim3(ga.G), dim3(256), FV_WIDE_SMEM_FLOATS(TB) * 4, c->stream, ga);
+    return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
+}
+
+// GEMM kernel used up to 64 tokens (above that always the shared-activation kernel)
+enum GemmKind { GEMM_SHARED = 0, GEMM_DIRECT = 1, GEMM_WIDE = 2 };
+
 template <typename EL, int D, int EPI>
-int launch_gemm(fv_ctx* c, int Tp, const GemmArgs& ga, bool direct) {
-    if (direct) return Tp == 32 ? launch_gemm_direct_t<EL, 1, D, EPI>(c, ga) : launch_gemm_direct_t<EL, 2, D, EPI>(c, ga);
+int launch_gemm(fv_ctx* c, int Tp, const GemmArgs& ga, int kind) {
+    if (kind == GEMM_DIRECT) return Tp == 32 ? launch_gemm_direct_t<EL, 1, D, EPI>(c, ga) : launch_gemm_direct_t<EL, 2, D, EPI>(c, ga);
+    if (kind == GEMM_WIDE) return Tp == 32 ? launch_gemm_wide_t<EL, 1, D, EPI>(c, ga) : launch_gemm_wide_t<EL, 2, D, EPI>(c, ga);
     switch (Tp) {
         case 32: return launch_gemm_t<EL, 1, D, EPI>(c, ga);
         case 64: return launch_gemm_t<EL, 2, D, EPI>(c, ga);
@@ -296,6 +306,8 @@ int set_gemm_attrs_e() {
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 4, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 256));
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm_direct<EL, 1, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_DIRECT_SMEM_FLOATS(1) * 4));
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm_direct<EL, 2, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_DIRECT_SMEM_FLOATS(2) * 4));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm_wide<EL, 1, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_WIDE_SMEM_FLOATS(1) * 4));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm_wide<EL, 2, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_WIDE_SMEM_FLOATS(2) * 4));
     return FV_OK;
 }
 template <typename EL, int D>
@@ -401,9 +413,9 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
     }
     HIPCHK(hipGetLastError());
 
-    const bool direct = (Tp <= 64) && !c->force_shared;
+    const int direct = (Tp <= 64) ? c->gemm_kind : GEMM_SHARED;
     auto gemm_args = [&](int which, const void* Wt, size_t x_off) {
-        const GemmPlan& p = direct ? ly.gd[which] : ly.gm[which];
+        const GemmPlan& p = (direct == GEMM_DIRECT) ? ly.gd[which] : ly.gm[which];
         GemmArgs ga;
         memset(&ga, 0, sizeof(ga));
         ga.Wt = (const uint4*)Wt; ga.X = c->at<uint4>(x_off); ga.part = c->at<float>(ly.off_part);
@@ -664,7 +676,7 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     if (arena_bytes < c->lay.total) { delete c; return FV_E_BAD_ARG; }
     c->arena = (char*)dev_arena;
     c->stream = (hipStream_t)hip_stream;
-    { const char* e = getenv("FV_GEMM"); c->force_shared = e && !strcmp(e, "shared"); }
+    { const char* e = getenv("FV_GEMM"); c->gemm_kind = !e ? GEMM_DIRECT : !strcmp(e, "shared") ? GEMM_SHARED : !strcmp(e, "wide") ? GEMM_WIDE : GEMM_DIRECT; }
     { const char* e = getenv("FV_PERSISTENT"); if (e && !strcmp(e, "0")) c->persistent_ok = false; }
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);

@@ -284,21 +284,15 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         __syncthreads();   // the slot and ticket_lds are reused
     };
 
-#ifndef FVD_MMA
-#define FVD_MMA(c, a_, b_) c = Tr<EL>::mma(a_, b_, c)
-#endif
-#ifndef FVD_LOADX
-#define FVD_LOADX(d, c) load_x(d, c)
-#endif
 #define FV_DSTAGE(S)                                                                        \
     {                                                                                       \
         if (cc.s < nseg) {                                                                  \
             _Pragma("unroll") for (int f = 0; f < FV_FRAGS; ++f)                            \
                 _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                           \
-                    FVD_MMA(acc[tb], w[S][f], x[S][f * TB + tb]);                           \
+                    acc[tb] = Tr<EL>::mma(w[S][f], x[S][f * TB + tb], acc[tb]);             \
         }                                                                                   \
         __builtin_amdgcn_sched_barrier(0);                                                  \
-        FVD_LOADX(x[S], cx); cur_next(cx);                                                  \
+        load_x(x[S], cx); cur_next(cx);                                                     \
         __builtin_amdgcn_sched_barrier(0);                                                  \
         load_w(w[S], cw); cur_next(cw);                                                     \
         __builtin_amdgcn_sched_barrier(0);                                                  \

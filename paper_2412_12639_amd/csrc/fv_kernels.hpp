@@ -470,6 +470,7 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
 }
 
 #include "fv_gemm_direct.hpp"
+#include "fv_gemm_wide.hpp"
 
 // ============================================================================ tree attention
 // For node t and query head qh: softmax over {cache slots 0..L-1} U {tree slots L+j : j in

@@ -278,3 +278,25 @@ def test_persistent_kernel_and_per_gemm_path_agree(fvmod, name, monkeypatch):
         H.check_cache(g, case["oracle"], s, 70 + got[0] + 1, tol)
         g.close()
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
+@pytest.mark.parametrize("kind", ["wide", "shared"])
+@pytest.mark.parametrize("name", ["tiny", "small-gqa", "small-gqa-f32"])
+def test_alternative_gemm_kernels_match_the_oracle(fvmod, name, kind, monkeypatch):
+    """Up to 64 tokens the GEMMs default to the direct-operand kernel; FV_GEMM selects the
+    four-strips-per-wavefront kernel ("wide") or the LDS-shared-activation kernel ("shared")
+    instead (per-GEMM launches).  Same bar against the oracle for each."""
+    s, w = SHAPES[name], weights_of(name)
+    tol = H.tol_for(s)
+    say("gemm-kind", kind, name)
+    monkeypatch.setenv("FV_GEMM", kind)
+    monkeypatch.setenv("FV_PERSISTENT", "0")
+    for n_nodes in (48, 17):
+        case = H.planted_case(s, w, 70, n_nodes, [6, 3, 2, 2, 1, 1], 3, seed=4)
+        g = make_gpu(fvmod, s, w, max_seq=160, max_tree=64)
+        assert g.prefill(case["prefix"]) == case["root"]
+        got = g.verify_tree(case["tokens"], case["parent"], case["depth"])
+        e = H.check_step(g, case, got, tol)
+        say("FV_GEMM=" + kind, n_nodes, "nodes: err", e)
+        H.check_cache(g, case["oracle"], s, 70 + got[0] + 1, tol)
+        g.close()
