@@ -87,6 +87,19 @@ def cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root, sample
     }
 
 
+def measured_traffic(kname, args, shape):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
+    (profiles/traffic_*.md: FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), if one
+    exists for exactly this workload and kernel; else None."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{shape.name}_prefix{args.prefix}_tree{args.nodes}.md")
+    if args.layers or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("TRAFFIC_BYTES_PER_LAUNCH") and kname.split()[0] in line:
+            return float(line.split("=")[1].split()[0])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +114,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers in the oracle's CPU-baseline sample (0 = skip)")
     ap.add_argument("--profile-steps", type=int, default=10)
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run three device-to-device copies of this many MiB (a kernel of known HBM traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -177,9 +193,14 @@ def main():
         kv_bytes = shape.n_layers * 2 * (L + T) * shape.n_kv_heads * shape.head_dim * shape.elem_bytes()
         bytes_per_launch = (weight_bytes - head_bytes + kv_bytes) / n_launch
     else:
-        kname = "k_gemm (weight-streaming skinny GEMM)"
+        # One launch per GEMM: the dominant kernel is the weight-streaming GEMM (129 launches per
+        # step stream all weights once).  Events around every single launch open gaps that inflate
+        # a per-launch figure, so its time is taken from the TIMED region instead: the step's device
+        # time between its two events, minus the attention and small-kernel time of the profiling pass.
+        kname = "k_gemm_direct (weight-streaming skinny GEMM, all five matrices of the step)"
         n_launch = ph["gemm"][1] / args.profile_steps
-        ms_per_launch = ph["gemm"][0] / max(1, ph["gemm"][1])
+        other_ms = (ph["attn"][0] + ph["other"][0] + ph["fixup"][0]) / args.profile_steps
+        ms_per_launch = (float(np.median(dev_ms)) - other_ms) / n_launch
         bytes_per_launch = weight_bytes / n_launch
     achieved = bytes_per_launch / (ms_per_launch * 1e-3) / 1e9
     step_bytes = shape.step_bytes(L, T)
@@ -209,8 +230,19 @@ def main():
                      "launches_per_step": n_launch},
         "phase_ms_per_step": {k: v[0] / args.profile_steps for k, v in ph.items()},
     }
+    traffic = measured_traffic(kname, args, shape)
+    if traffic is not None:
+        out["roofline"]["traffic"] = traffic
     if args.layers:
         out["invalid"] = "model truncated with --layers (debug run)"
+    if args.calib_copy_mb > 0:
+        n = args.calib_copy_mb << 20
+        src = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"calibration: 3 device copies of {n} bytes (reads {n}, writes {n} each)")
     if args.cpu_layers > 0:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root,

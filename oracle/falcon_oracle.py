@@ -32,11 +32,31 @@ greedy decoding; closed forms for the ancestor mask; cache contents after
 compaction against a fresh prefill of the extended sequence.
 
 Readings where the paper is silent are listed with each function.
+
+Precision.  The paper states none; the default is fp64 throughout.  `Oracle(storage="bf16")`
+is the same computation with the STORAGE FORMATS of the bf16 configuration written in: every
+tensor that such a configuration keeps in bf16 (the input of each weight multiplication, the
+rotated queries and keys, the values, i.e. the K/V cache, and the attention probabilities that
+multiply the values) is rounded to bf16 (round to nearest even) at the point where it is
+stored; all arithmetic stays in the working precision.  It exists for deep models, where the
+rounding noise of those formats alone (about 2^-9 relative per stored tensor, adding in
+quadrature over ~9 tensors per layer) exceeds the tolerance that is demanded of shallow ones;
+pinned in tests/test_oracle_pins.py (rounding against a library conversion; storage=None
+unchanged; exactly representable data unaffected).
 """
 import numpy as np
 
 
 # ----------------------------------------------------------------------------- helpers
+
+def round_bf16(x):
+    """Round to the nearest bf16 value, ties to even, through fp32 (the value is first an fp32
+    number, as on a device that computes in fp32); returned in x's own dtype."""
+    a = np.ascontiguousarray(x, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32).astype(np.asarray(x).dtype)
+
 
 def _up(w, dtype):
     """Weights arrive as float32 or as bf16 bit patterns (uint16); both are widened
@@ -165,8 +185,12 @@ class TreeVerifyError(ValueError):
 class Oracle:
     """prefill / verify_tree with a per-layer K/V cache (K stored after rotation)."""
 
-    def __init__(self, shape, weights, max_seq, dtype=np.float64):
+    def __init__(self, shape, weights, max_seq, dtype=np.float64, storage=None):
+        if storage not in (None, "bf16"):
+            raise ValueError("storage must be None or 'bf16'")
         self.s, self.w, self.dtype = shape, weights, dtype
+        self.st = round_bf16 if storage == "bf16" else (lambda t: t)
+        self.storage = storage
         s = shape
         self.K = np.zeros((s.n_layers, max_seq, s.n_kv_heads, s.head_dim), dtype=dtype)
         self.V = np.zeros_like(self.K)
@@ -182,12 +206,13 @@ class Oracle:
         newK = np.zeros((s.n_layers, n, s.n_kv_heads, s.head_dim), dtype=dt)
         newV = np.zeros_like(newK)
         grp = s.n_q_heads // s.n_kv_heads
+        st = self.st
         for l in range(s.n_layers):
             W = lambda k: self.w[f"l{l}.{k}"]
-            xn = rmsnorm(x, W("g_attn").astype(dt), s.rms_eps)
-            q = rope(linear(xn, W("wq"), dt).reshape(n, s.n_q_heads, s.head_dim), pos, s.rope_base)
-            k = rope(linear(xn, W("wk"), dt).reshape(n, s.n_kv_heads, s.head_dim), pos, s.rope_base)
-            v = linear(xn, W("wv"), dt).reshape(n, s.n_kv_heads, s.head_dim)
+            xn, post = self._norm_in(x, W("g_attn").astype(dt))
+            q = st(rope((linear(xn, W("wq"), dt) * post).reshape(n, s.n_q_heads, s.head_dim), pos, s.rope_base))
+            k = st(rope((linear(xn, W("wk"), dt) * post).reshape(n, s.n_kv_heads, s.head_dim), pos, s.rope_base))
+            v = st((linear(xn, W("wv"), dt) * post).reshape(n, s.n_kv_heads, s.head_dim))
             newK[l], newV[l] = k, v
             att = np.zeros((n, s.n_q_heads, s.head_dim), dtype=dt)
             for i in range(n):
@@ -198,14 +223,30 @@ class Oracle:
                 kq = np.repeat(keys, grp, axis=1)                         # [m, Hq, d]
                 vq = np.repeat(vals, grp, axis=1)
                 sc = np.einsum("hd,mhd->hm", q[i], kq) / np.sqrt(s.head_dim)
-                p = softmax_lastaxis(sc)
-                att[i] = np.einsum("hm,mhd->hd", p, vq)
-            x = x + linear(att.reshape(n, -1), W("wo"), dt)
-            xn = rmsnorm(x, W("g_mlp").astype(dt), s.rms_eps)
-            a = silu(linear(xn, W("wg"), dt)) * linear(xn, W("wu"), dt)
-            x = x + linear(a, W("wd"), dt)
-        xn = rmsnorm(x, self.w["g_final"].astype(dt), s.rms_eps)
-        return linear(xn, self.w["lm_head"], dt), newK, newV
+                if self.storage is None:
+                    p = softmax_lastaxis(sc)
+                    att[i] = np.einsum("hm,mhd->hd", p, vq)
+                else:
+                    # stored probabilities are the un-normalised exp(s - max); the sum that
+                    # normalises them is taken before they are rounded
+                    e = np.exp(sc - np.max(sc, axis=-1, keepdims=True))
+                    att[i] = np.einsum("hm,mhd->hd", st(e), vq) / np.sum(e, axis=-1, keepdims=True)
+            x = x + linear(st(att.reshape(n, -1)), W("wo"), dt)
+            xn, post = self._norm_in(x, W("g_mlp").astype(dt))
+            a = silu(linear(xn, W("wg"), dt) * post) * (linear(xn, W("wu"), dt) * post)
+            x = x + linear(st(a), W("wd"), dt)
+        xn, post = self._norm_in(x, self.w["g_final"].astype(dt))
+        return linear(xn, self.w["lm_head"], dt) * post, newK, newV
+
+    def _norm_in(self, x, gain):
+        """RMSNorm as the input of a weight multiplication: returns (input, factor) with
+        norm(x) W^T == (input W^T) * factor.  Default: (rmsnorm(x), 1).  With bf16 storage the
+        stored tensor is x * gain (rounded), and the per-row factor 1/sqrt(mean(x^2) + eps)
+        multiplies the product, which is the same thing in exact arithmetic."""
+        if self.storage is None:
+            return rmsnorm(x, gain, self.s.rms_eps), 1.0
+        rinv = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + self.s.rms_eps)
+        return self.st(x * gain), rinv
 
     def prefill(self, tokens):
         """Run the prompt, fill cache slots 0..n-1, return the greedy next token (the

@@ -358,3 +358,69 @@ def test_bf16_weights_are_consumed_bit_exactly():
     w32 = {k: (fi.f32_from_bf16_bits(v) if v.dtype == np.uint16 else v) for k, v in w16.items()}
     toks = fi.gen_prefix(1, 9, s16.vocab)
     assert np.array_equal(fo.causal_forward(s16, w16, toks), fo.causal_forward(fi.SHAPES["tiny"], w32, toks))
+
+
+# ---- bf16 storage model of the oracle (deep bf16 configurations)
+
+def test_round_bf16_matches_library_conversion():
+    """Round-to-nearest-even to bf16, against torch's conversion: random values over many binades,
+    exact ties in both directions, signed zeros, values that round up into the next binade."""
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(20000) * np.exp(rng.uniform(-30, 30, 20000))).astype(np.float32)
+    ties = np.array([0x3F808000, 0x3F818000, 0xBF808000, 0xBF818000, 0x3FFF8000, 0x3FFFFFFF, 0x00000000, 0x80000000,
+                     0x3F807FFF, 0x3F808001], dtype=np.uint32).view(np.float32)
+    x = np.concatenate([x, ties])
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    got = fo.round_bf16(x)
+    assert got.dtype == np.float32 and np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    got64 = fo.round_bf16(x.astype(np.float64))
+    assert got64.dtype == np.float64 and np.array_equal(got64, ref.astype(np.float64))
+    # the two tie cases by hand: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> even mantissa (1.0);
+    # 1 + 3*2^-8 is halfway between 1 + 2^-7 and 1 + 2^-6 -> even mantissa (1 + 2^-6)
+    assert fo.round_bf16(np.float32(1 + 2.0 ** -8)) == 1.0
+    assert fo.round_bf16(np.float32(1 + 3 * 2.0 ** -8)) == np.float32(1 + 2.0 ** -6)
+
+
+def test_bf16_storage_model_keeps_the_method_invariants(small):
+    """With storage rounding written in, the step is still the same method: every node's logits are
+    those of a plain prefill (same storage model) over prefix ++ root path, and a chain tree
+    reproduces single-token decoding token for token.  And the result sits at rounding distance from
+    the fp64 one: not equal, not far."""
+    s, w, prefix = small
+    o, root, greedy, parent, depth, planted, tok = _planted_tree(s, w, prefix, 0, 16, [4, 2, 1, 1], 3)
+    ob = fo.Oracle(s, w, max_seq=len(prefix) + 40, storage="bf16")
+    rootb = ob.prefill(prefix)
+    r64 = o.verify_tree(tok, parent, depth)
+    if rootb == root:
+        rb = ob.verify_tree(tok, parent, depth)
+        err = np.max(np.abs(rb["logits"] - r64["logits"]), axis=-1) / np.max(np.abs(r64["logits"]), axis=-1)
+        assert 1e-4 < err.max() < 2e-2
+        ob.rollback(len(prefix), rootb)
+    # brute force in the same storage model
+    tok_b = np.array(tok).copy()
+    tok_b[0] = rootb
+    rb = ob.verify_tree(tok_b, parent, depth)
+    for i in (0, 3, 9, 15):
+        seq = list(prefix) + [int(tok_b[j]) for j in fo.root_path(parent, i)]
+        o2 = fo.Oracle(s, w, max_seq=len(seq) + 4, storage="bf16")
+        o2.prefill(seq)
+        ref = o2.last_logits[-1]
+        assert np.max(np.abs(rb["logits"][i] - ref)) < 1e-9 * np.max(np.abs(ref))
+    # chain == one token at a time
+    o3 = fo.Oracle(s, w, max_seq=len(prefix) + 40, storage="bf16")
+    t0 = o3.prefill(prefix)
+    seq, tk = [], t0
+    p1, d1 = fi.chain_tree(1)
+    for _ in range(4):
+        tk = o3.verify_tree(np.array([tk], dtype=np.int32), p1, d1)["next_token"]
+        seq.append(tk)
+    o3.rollback(len(prefix), t0)
+    pc, dc = fi.chain_tree(4)
+    rc = o3.verify_tree(np.array([t0] + seq[:3], dtype=np.int32), pc, dc)
+    assert rc["accepted_len"] == 3 and rc["next_token"] == seq[3]
+
+
+def test_storage_argument_is_checked(tiny):
+    s, w, prefix = tiny
+    with pytest.raises(ValueError):
+        fo.Oracle(s, w, max_seq=80, storage="fp8")
