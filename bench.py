@@ -109,7 +109,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="truncate the model (debug only; marks the line invalid)")
     ap.add_argument("--prefix", type=int, default=512)
     ap.add_argument("--nodes", type=int, default=64)
-    ap.add_argument("--branching", default="8,4,2,2,1,1")
+    ap.add_argument("--branching", default="8,4,2,2,1,1",
+                    help="children per level, or 'random' (per-level branching uniform in [1, 8], depth <= 8, seeded)")
     ap.add_argument("--plant", type=int, default=3)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers in the oracle's CPU-baseline sample (0 = skip)")
@@ -135,13 +136,15 @@ def main():
     shape = fi.SHAPES[args.shape]
     if args.layers:
         shape = shape.with_layers(args.layers)
-    branching = [int(x) for x in args.branching.split(",")]
+    branching = (fi.random_branching(args.seed, args.nodes) if args.branching == "random"
+                 else [int(x) for x in args.branching.split(",")])
     L, T = args.prefix, args.nodes
 
     t0 = time.time()
     weights = fi.gen_weights(shape, seed=args.seed)
     log(f"weights generated on the host in {time.time() - t0:.1f} s ({shape.weight_params() * shape.elem_bytes() / 1e9:.2f} GB)")
     max_tree = 256
+    assert T <= max_tree
     gpu = m.FalconVerifier(shape, max_seq=L + max_tree + 8, max_tree=max_tree)
     t0 = time.time()
     gpu.init_weights(weights)

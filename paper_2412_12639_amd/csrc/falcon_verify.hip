@@ -29,6 +29,7 @@ struct GemmPlan {
     int K = 0, Kpad = 0, NB = 0;
     int n_strips = 0, n_strips_pad = 0, NG = 0;
     int G = 0, segmax = 0;
+    int aligned = 0;   // workgroup ranges end on row-group boundaries
     size_t tiled_bytes = 0;
     size_t off_tab = 0;   // device tables: u0[G+1], g0[G], cf[NG], cl[NG]
 };
@@ -39,6 +40,8 @@ struct Layout {
     int E = 0, ESZ = 0, Tpm = 0, S_pad = 0, Vpad = 0;
     GemmPlan gm[GM_COUNT];    // shared-activation kernel (row groups of FV_R strips)
     GemmPlan gd[GM_COUNT];    // direct kernel (one strip per workgroup at a time), used up to 64 tokens
+    GemmPlan gp[GM_COUNT];    // paired form of it (two strips per wavefront, half-batch stages)
+    bool paired_ok[GM_COUNT]; // the paired form's two staging slots suffice for this matrix
     size_t layer_w_bytes = 0;        // tiled weights of one layer
     size_t off_w[4] = {0, 0, 0, 0};  // offsets of QKV, O, GU, DN inside a layer
     size_t off_layers = 0, off_lm = 0, off_embed = 0, off_gains = 0;
@@ -49,7 +52,7 @@ struct Layout {
     size_t off_kvread = 0, off_stage = 0, stage_bytes = 0;
     // persistent step kernel: rotating activation slots (one per layer + 1), barrier words, error flag
     size_t off_rot = 0, rot_stride = 0, o_xa = 0, o_xm = 0, o_xba = 0, o_xbm = 0, o_ssqa = 0, o_ssqm = 0, o_q = 0, o_attn = 0, o_act = 0;
-    size_t off_bar = 0, off_err = 0, off_tstamp = 0, off_apart = 0, off_atick = 0;
+    size_t off_bar = 0, off_err = 0, off_tstamp = 0, off_apart = 0, off_atick = 0, off_zeros = 0;
     size_t total = 0;
 };
 
@@ -73,11 +76,13 @@ int pad_tokens(int n) {   // token count padded to 32, 64, 128 or 256
     return tp;
 }
 
-void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R) {
+// R strips per row group; stage_frags fragments (of 2E columns) per K step of the split (the
+// tiled buffer itself is always padded to whole 8-fragment batches)
+void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R, int stage_frags = FV_FRAGS) {
     const int KB = 16 * E;
     p.K = K;
     p.Kpad = (int)rup(K, KB);
-    p.NB = p.Kpad / KB;
+    p.NB = p.Kpad / (2 * E * stage_frags);
     p.n_strips = n_strips;
     p.n_strips_pad = (int)rup(n_strips, FV_R);   // the tiled buffer always holds whole groups of FV_R strips
     p.NG = (R == 1) ? n_strips : p.n_strips_pad / R;
@@ -85,7 +90,8 @@ void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R) 
     p.G = (int)(U < n_wg ? U : n_wg);
     const long long per = (U + p.G - 1) / p.G;
     p.segmax = (int)((per + p.NB - 1) / p.NB) + 1;
-    p.tiled_bytes = (size_t)p.n_strips_pad * p.NB * FV_FRAGS * 1024;
+    p.aligned = 0;
+    p.tiled_bytes = (size_t)p.n_strips_pad * (p.Kpad / KB) * FV_FRAGS * 1024;
 }
 
 // The stream-K split of one GEMM: workgroup w owns units [u0[w], u0[w+1]) of the (row group,
@@ -97,7 +103,7 @@ void build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
     int* g0 = u0 + p.G + 1;
     int* cf = g0 + p.G;
     int* cl = cf + p.NG;
-    for (int w = 0; w <= p.G; ++w) u0[w] = (int)(U * w / p.G);
+    for (int w = 0; w <= p.G; ++w) u0[w] = p.aligned ? (int)((long long)p.NG * w / p.G) * p.NB : (int)(U * w / p.G);
     for (int w = 0; w < p.G; ++w) g0[w] = u0[w] / p.NB;
     for (int gi = 0; gi < p.NG; ++gi) { cf[gi] = p.G; cl[gi] = -1; }
     for (int w = 0; w < p.G; ++w)
@@ -118,7 +124,25 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     plan_gemm(L.gm[GM_GU], c.ffn / 16, c.hidden, L.E, n_wg);
     plan_gemm(L.gm[GM_DN], c.hidden / 32, c.ffn, L.E, n_wg);
     plan_gemm(L.gm[GM_LM], (c.vocab + 31) / 32, c.hidden, L.E, n_wg);
-    for (int i = 0; i < GM_COUNT; ++i) plan_gemm(L.gd[i], L.gm[i].n_strips, L.gm[i].K, L.E, n_wg, 1);
+    for (int i = 0; i < GM_COUNT; ++i) {
+        plan_gemm(L.gd[i], L.gm[i].n_strips, L.gm[i].K, L.E, n_wg, 1);
+        plan_gemm(L.gp[i], L.gm[i].n_strips, L.gm[i].K, L.E, n_wg, 2, FV_FRAGS / 2);
+        // a full K range must give each of the four wavefronts at least three stages, so that no
+        // wavefront meets more than two segment ends within one round of three stages
+        L.paired_ok[i] = L.gp[i].NB >= 12;
+        // Whole row groups per workgroup need no partial-tile exchange at all, but the group counts
+        // differ by one between workgroups: worth it only when that idles little of the chip (the
+        // LM head: 500 groups of 64 rows over 256 workgroups).  (FV_GEMM_ALIGN=0 / 1 forces it off / on.)
+        const char* al = getenv("FV_GEMM_ALIGN");
+        for (GemmPlan* q : {&L.gd[i], &L.gp[i]}) {
+            if (q->NG < q->G) continue;
+            const int per = (q->NG + q->G - 1) / q->G;
+            const double idle = (double)((long long)per * q->G - q->NG) / (double)q->NG;
+            q->aligned = al ? (!strcmp(al, "1") ? 1 : 0) : (idle <= 0.10 ? 1 : 0);
+        }
+        for (GemmPlan* q : {&L.gd[i], &L.gp[i]})
+            if (q->aligned) q->segmax = (q->NG + q->G - 1) / q->G + 1;
+    }
     L.Vpad = L.gm[GM_LM].n_strips * 32;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o = rup(o + bytes, 256); return r; };
@@ -147,6 +171,8 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
         if (b > pb) pb = b;
         const size_t bd = (size_t)L.gd[i].G * L.gd[i].segmax * 2 * 4096;
         if (bd > pb) pb = bd;
+        const size_t bp = (size_t)L.gp[i].G * L.gp[i].segmax * 4 * 4096;
+        if (bp > pb) pb = bp;
     }
     L.part_bytes = pb;
     L.off_part = take(pb);
@@ -156,7 +182,9 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     for (int i = 0; i < GM_COUNT; ++i) {
         L.gm[i].off_tab = take((size_t)(2 * L.gm[i].G + 1 + 2 * L.gm[i].NG) * 4);
         L.gd[i].off_tab = take((size_t)(2 * L.gd[i].G + 1 + 2 * L.gd[i].NG) * 4);
+        L.gp[i].off_tab = take((size_t)(2 * L.gp[i].G + 1 + 2 * L.gp[i].NG) * 4);
     }
+    L.off_zeros = take(32768);   // never written after the arena is cleared
     L.off_stepin = take(3 * FV_MAX_TREE * 4);
     L.off_mask = take(FV_MAX_TREE * 4 * 8);
     L.off_pos = take(FV_MAX_TREE * 4);
@@ -228,7 +256,7 @@ struct fv_ctx {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     float last_ms = 0.f;
     bool profiling = false;
-    int gemm_kind = 1;        // GemmKind used up to 64 tokens
+    int kind[GM_COUNT];       // GemmKind per matrix, used up to 64 tokens
     bool persistent_ok = false;  // persistent step kernel asked for (FV_PERSISTENT=1) and cooperative launch available
     bool last_persistent = false;
     unsigned bar_gen = 0;
@@ -284,11 +312,18 @@ int launch_gemm_wide_t(fv_ctx* c, const GemmArgs& ga) {
 }
 
 // GEMM kernel used up to 64 tokens (above that always the shared-activation kernel)
-enum GemmKind { GEMM_SHARED = 0, GEMM_DIRECT = 1, GEMM_WIDE = 2 };
+enum GemmKind { GEMM_SHARED = 0, GEMM_DIRECT = 1, GEMM_WIDE = 2, GEMM_PAIRED = 3 };
+
+template <typename EL, int TB, int D, int EPI>
+int launch_gemm_paired_t(fv_ctx* c, const GemmArgs& ga) {
+    hipLaunchKernelGGL((k_gemm_paired<EL, TB, D, EPI>), dim3(ga.G), dim3(256), FV_PAIRED_SMEM_FLOATS(TB) * 4, c->stream, ga);
+    return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
+}
 
 template <typename EL, int D, int EPI>
 int launch_gemm(fv_ctx* c, int Tp, const GemmArgs& ga, int kind) {
     if (kind == GEMM_DIRECT) return Tp == 32 ? launch_gemm_direct_t<EL, 1, D, EPI>(c, ga) : launch_gemm_direct_t<EL, 2, D, EPI>(c, ga);
+    if (kind == GEMM_PAIRED) return Tp == 32 ? launch_gemm_paired_t<EL, 1, D, EPI>(c, ga) : launch_gemm_paired_t<EL, 2, D, EPI>(c, ga);
     if (kind == GEMM_WIDE) return Tp == 32 ? launch_gemm_wide_t<EL, 1, D, EPI>(c, ga) : launch_gemm_wide_t<EL, 2, D, EPI>(c, ga);
     switch (Tp) {
         case 32: return launch_gemm_t<EL, 1, D, EPI>(c, ga);
@@ -306,6 +341,8 @@ int set_gemm_attrs_e() {
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm<EL, 4, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 128 * 256));
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm_direct<EL, 1, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_DIRECT_SMEM_FLOATS(1) * 4));
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm_direct<EL, 2, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_DIRECT_SMEM_FLOATS(2) * 4));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm_paired<EL, 1, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PAIRED_SMEM_FLOATS(1) * 4));
+    HIPCHK(hipFuncSetAttribute((const void*)k_gemm_paired<EL, 2, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PAIRED_SMEM_FLOATS(2) * 4));
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm_wide<EL, 1, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_WIDE_SMEM_FLOATS(1) * 4));
     HIPCHK(hipFuncSetAttribute((const void*)k_gemm_wide<EL, 2, D, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_WIDE_SMEM_FLOATS(2) * 4));
     return FV_OK;
@@ -356,7 +393,7 @@ int launch_persistent(fv_ctx* c, int T, int Tp, int L) {
     pa.rot = c->arena + ly.off_rot; pa.rot_stride = ly.rot_stride;
     pa.o_xa = ly.o_xa; pa.o_xm = ly.o_xm; pa.o_xba = ly.o_xba; pa.o_xbm = ly.o_xbm; pa.o_ssqa = ly.o_ssqa; pa.o_ssqm = ly.o_ssqm;
     pa.o_q = ly.o_q; pa.o_attn = ly.o_attn; pa.o_act = ly.o_act;
-    pa.part = c->at<float>(ly.off_part); pa.tickets = c->at<int>(ly.off_tickets);
+    pa.part = c->at<float>(ly.off_part); pa.tickets = c->at<int>(ly.off_tickets); pa.zeros = c->at<uint4>(ly.off_zeros);
     pa.attn_part = c->at<float>(ly.off_apart); pa.attn_tickets = c->at<int>(ly.off_atick);
     pa.attn_ks = attn_key_split(cf.n_q_heads * (Tp / 32), L + T, 256);
     pa.bar = c->at<unsigned>(ly.off_bar); pa.gen0 = c->bar_gen; pa.err = c->at<int>(ly.off_err);
@@ -365,7 +402,7 @@ int launch_persistent(fv_ctx* c, int T, int Tp, int L) {
     int grid = 1;
     for (int i = 0; i < 4; ++i) {
         const GemmPlan& p = ly.gd[i];
-        pa.g[i].NG = p.NG; pa.g[i].NB = p.NB; pa.g[i].G = p.G; pa.g[i].segmax = p.segmax; pa.g[i].n_strips = p.n_strips;
+        pa.g[i].NG = p.NG; pa.g[i].NB = p.NB; pa.g[i].G = p.G; pa.g[i].segmax = p.segmax; pa.g[i].n_strips = p.n_strips; pa.g[i].aligned = p.aligned;
         pa.g[i].tab = c->at<int>(p.off_tab);
         if (p.G > grid) grid = p.G;
     }
@@ -413,14 +450,16 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
     }
     HIPCHK(hipGetLastError());
 
-    const int direct = (Tp <= 64) ? c->gemm_kind : GEMM_SHARED;
+    // kernel per matrix: above 64 tokens always the shared-activation kernel
+    auto kind_of = [&](int which) { return (Tp <= 64) ? c->kind[which] : (int)GEMM_SHARED; };
     auto gemm_args = [&](int which, const void* Wt, size_t x_off) {
-        const GemmPlan& p = (direct == GEMM_DIRECT) ? ly.gd[which] : ly.gm[which];
+        const int kind = kind_of(which);
+        const GemmPlan& p = (kind == GEMM_DIRECT) ? ly.gd[which] : (kind == GEMM_PAIRED) ? ly.gp[which] : ly.gm[which];
         GemmArgs ga;
         memset(&ga, 0, sizeof(ga));
         ga.Wt = (const uint4*)Wt; ga.X = c->at<uint4>(x_off); ga.part = c->at<float>(ly.off_part);
-        ga.tickets = c->at<int>(ly.off_tickets);
-        ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax;
+        ga.tickets = c->at<int>(ly.off_tickets); ga.zeros = c->at<uint4>(ly.off_zeros);
+        ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax; ga.aligned = p.aligned;
         ga.tab_u0 = c->at<int>(p.off_tab); ga.tab_g0 = ga.tab_u0 + p.G + 1; ga.tab_cf = ga.tab_g0 + p.G; ga.tab_cl = ga.tab_cf + p.NG;
         ga.T = T; ga.n_strips = p.n_strips;
         ga.ssq_in = c->at<float>(ly.off_ssq); ga.n_ssq = h / 32; ga.inv_h = 1.f / (float)h; ga.eps = cf.rms_eps;
@@ -450,7 +489,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             GemmArgs ga = gemm_args(GM_QKV, c->layer_w(l, 0), ly.off_xb);
             ga.q_out = c->at<void>(ly.off_q); ga.kcache = c->kc(l); ga.vcache = c->vc(l);
             ga.rope_cs = c->at<float2>(ly.off_rope); ga.Hq = cf.n_q_heads; ga.Hkv = cf.n_kv_heads; ga.L = L; ga.S_pad = ly.S_pad;
-            rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, direct);
+            rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, kind_of(GM_QKV));
             if (rc) return rc;
         }
         {
@@ -470,14 +509,14 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             GemmArgs ga = gemm_args(GM_O, c->layer_w(l, 1), ly.off_attn);
             ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb); ga.gain_next = c->gain(2 * l + 1);
             ga.ssq_out = c->at<float>(ly.off_ssq);
-            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, direct);
+            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, kind_of(GM_O));
             if (rc) return rc;
         }
         {   // gate and up projections, SwiGLU
             PhaseTimer pt(c, FV_PH_GEMM);
             GemmArgs ga = gemm_args(GM_GU, c->layer_w(l, 2), ly.off_xb);
             ga.act = c->at<void>(ly.off_act);
-            rc = launch_gemm<EL, D, EPI_SWIGLU>(c, Tp, ga, direct);
+            rc = launch_gemm<EL, D, EPI_SWIGLU>(c, Tp, ga, kind_of(GM_GU));
             if (rc) return rc;
         }
         {   // down projection, residual add, statistics + input of the next norm
@@ -486,7 +525,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb);
             ga.gain_next = (l + 1 < cf.n_layers) ? c->gain(2 * (l + 1)) : c->gain(2 * cf.n_layers);
             ga.ssq_out = c->at<float>(ly.off_ssq);
-            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, direct);
+            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, kind_of(GM_DN));
             if (rc) return rc;
         }
     }
@@ -497,7 +536,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             GemmArgs ga = gemm_args(GM_LM, c->at<void>(ly.off_lm), persistent ? last_slot + ly.o_xba : ly.off_xb);
             if (persistent) ga.ssq_in = (const float*)(c->arena + last_slot + ly.o_ssqa);
             ga.logits = c->at<float>(ly.off_logits); ga.Vpad = ly.Vpad;
-            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, direct);
+            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, kind_of(GM_LM));
             if (rc) return rc;
         }
         PhaseTimer pt(c, FV_PH_OTHER);
@@ -676,7 +715,19 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     if (arena_bytes < c->lay.total) { delete c; return FV_E_BAD_ARG; }
     c->arena = (char*)dev_arena;
     c->stream = (hipStream_t)hip_stream;
-    { const char* e = getenv("FV_GEMM"); c->gemm_kind = !e ? GEMM_DIRECT : !strcmp(e, "shared") ? GEMM_SHARED : !strcmp(e, "wide") ? GEMM_WIDE : GEMM_DIRECT; }
+    {   // GEMM kernel up to 64 tokens.  Default: the paired form wherever its staging slots suffice.
+        // FV_GEMM = direct | paired | wide | shared forces one kind; FV_GEMM_PAIRED_SET = bit mask over
+        // (QKV, O, gate/up, down, head) restricts the paired form to those matrices (tuning aid).
+        const char* e = getenv("FV_GEMM");
+        const int kind = !e ? GEMM_PAIRED : !strcmp(e, "shared") ? GEMM_SHARED : !strcmp(e, "wide") ? GEMM_WIDE
+                       : !strcmp(e, "direct") ? GEMM_DIRECT : GEMM_PAIRED;
+        const char* m = getenv("FV_GEMM_PAIRED_SET");
+        const int mask = m ? atoi(m) : 31;
+        for (int i = 0; i < GM_COUNT; ++i) {
+            c->kind[i] = kind;
+            if (kind == GEMM_PAIRED && (!c->lay.paired_ok[i] || !((mask >> i) & 1))) c->kind[i] = GEMM_DIRECT;
+        }
+    }
     // One launch per GEMM is the default: measured on the 7B shape it is ~6% faster per step than
     // the persistent kernel (which wins nothing from its cheaper phase boundaries once 32 layers of
     // rotating activation slots stop fitting the L2s).  FV_PERSISTENT=1 selects the persistent kernel.
@@ -697,8 +748,8 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     const size_t z0 = c->lay.off_gains;
     if (hipMemsetAsync(c->arena + z0, 0, c->lay.total - z0, c->stream) != hipSuccess) return fail(FV_E_HIP);
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(FV_E_HIP);
-    for (int k = 0; k < 2 * GM_COUNT; ++k) {
-        const GemmPlan& p = (k < GM_COUNT) ? c->lay.gm[k] : c->lay.gd[k - GM_COUNT];
+    for (int k = 0; k < 3 * GM_COUNT; ++k) {
+        const GemmPlan& p = (k < GM_COUNT) ? c->lay.gm[k] : (k < 2 * GM_COUNT) ? c->lay.gd[k - GM_COUNT] : c->lay.gp[k - 2 * GM_COUNT];
         std::vector<int> tab;
         build_split_tables(p, tab);
         if (hipMemcpy(c->arena + p.off_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return fail(FV_E_HIP);

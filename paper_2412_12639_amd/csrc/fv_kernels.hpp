@@ -103,15 +103,16 @@ enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 struct GemmArgs {
     const uint4* Wt;     // tiled weights [NG*R strips][NB][FRAGS][64] x 16 B
     const uint4* X;      // vector-major [NB*16][Tp] x 16 B
+    const uint4* zeros;  // 32 KiB of zeros (what the direct kernels' padded stages load)
     float* part;         // [G][segmax][R][TB][64][16] fp32
     int* tickets;        // [NG], zero on entry, left zero on exit
     int NG, NB, G, segmax;
+    int aligned;         // direct kernels: workgroup ranges end on row-group boundaries (no partial tiles)
     // stream-K split, precomputed on the host: range start of every workgroup (G+1 entries), its
     // first row group, and the first / last contributing workgroup of every row group
     const int* tab_u0; const int* tab_g0; const int* tab_cf; const int* tab_cl;
     int T, n_strips;     // real tokens; strips that carry real rows
     int epi;             // epilogue, for bodies that choose it at run time
-    long long* ts;       // optional time stamps (tuning), else null
     // RMSNorm statistics of the input (QKV, SWIGLU, LOGITS): rinv[t] = rsqrt(sum_s ssq_in[s][t] / h + eps)
     const float* ssq_in; // [n_ssq][Tp]
     int n_ssq;

@@ -3,8 +3,7 @@
 // One workgroup per compute unit, launched cooperatively (the runtime refuses the launch unless
 // every workgroup is resident), loops over the layers; the phases of a layer -- QKV GEMM, tree
 // attention, O GEMM, gate/up GEMM, down GEMM -- are separated by a grid barrier instead of a
-// kernel boundary, which costs about a third of one and lets the weight stream of the next
-// phase start before the barrier.
+// kernel boundary, which costs about a third of one.
 //
 // Visibility across workgroups inside a launch.  The XCDs' L2 caches are not coherent with each
 // other, and a whole-L2 write-back / invalidate per workgroup per phase is far too slow.  So
@@ -18,7 +17,7 @@
 // (included from fv_kernels.hpp after the GEMM and attention bodies)
 
 struct PersistGemm {          // stream-K plan of one GEMM type
-    int NG, NB, G, segmax, n_strips;
+    int NG, NB, G, segmax, n_strips, aligned;
     const int* tab;           // u0[G+1], g0[G], cf[NG], cl[NG]
 };
 
@@ -33,7 +32,7 @@ struct PersistArgs {
     const uint64_t* mask;
     // rotating activations: one slot per layer (+1), offsets of each buffer inside a slot
     char* rot; size_t rot_stride, o_xa, o_xm, o_xba, o_xbm, o_ssqa, o_ssqm, o_q, o_attn, o_act;
-    float* part; int* tickets;
+    float* part; int* tickets; const uint4* zeros;
     float* attn_part; int* attn_tickets; int attn_ks;
     unsigned* bar;            // [0] release word, slots at bar[64 + 32*b]
     unsigned gen0;            // barrier generation before this launch
@@ -108,7 +107,7 @@ __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
         const PersistGemm& p = a.g[which];
         GemmArgs ga;
         ga.Wt = (const uint4*)(a.w_layers + (size_t)l * a.layer_w_bytes + a.off_w[which]);
-        ga.part = a.part; ga.tickets = a.tickets;
+        ga.part = a.part; ga.tickets = a.tickets; ga.zeros = a.zeros;
         ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax;
         ga.tab_u0 = p.tab; ga.tab_g0 = p.tab + p.G + 1; ga.tab_cf = ga.tab_g0 + p.G; ga.tab_cl = ga.tab_cf + p.NG;
         ga.T = a.T; ga.n_strips = p.n_strips;
@@ -116,7 +115,7 @@ __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
         ga.Hq = a.Hq; ga.Hkv = a.Hkv; ga.L = a.L; ga.S_pad = a.S_pad; ga.rope_cs = a.rope_cs;
         ga.kcache = a.kc + (size_t)l * a.kv_layer_bytes; ga.vcache = a.vc + (size_t)l * a.kv_layer_bytes;
         ga.q_out = rs + a.o_q; ga.act = rs + a.o_act;
-        ga.logits = nullptr; ga.Vpad = 0; ga.ts = nullptr;
+        ga.logits = nullptr; ga.Vpad = 0; ga.aligned = p.aligned;
         ga.x_in = nullptr; ga.x = nullptr; ga.xb = nullptr; ga.gain_next = nullptr; ga.ssq_out = nullptr; ga.ssq_in = nullptr;
         if (k == 0) {          // normalised input of the layer -> rotated q, k/v into the cache
             ga.epi = EPI_QKV;
@@ -140,20 +139,11 @@ __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
 
     // Phases 0..4 of layer l: QKV, attention, O, gate/up, down.  One loop, so that the GEMM body
     // (the bulk of the code) is instantiated once and the kernel stays inside the instruction cache.
-    // The first three weight batches of the NEXT GEMM are requested before the barrier that ends a
-    // phase (weights do not depend on activations), so HBM keeps streaming through the barrier.
-    uint4 w[3][FV_FRAGS];
-    bool preloaded = false;
     const int n_phases = 5 * a.n_layers;
     for (int ph = 0; ph < n_phases; ++ph) {
         const int l = ph / 5, k = ph - 5 * l;
         if (k == 1) {
-            // tree attention: (head, 32-node block, key part) units round-robin over the workgroups.
-            // (Nothing is prefetched across this phase: say so, or the weight registers stay reserved.)
-#pragma unroll
-            for (int i = 0; i < 3; ++i)
-#pragma unroll
-                for (int f = 0; f < FV_FRAGS; ++f) w[i][f] = make_uint4(0u, 0u, 0u, 0u);
+            // tree attention: (head, 32-node block, key part) units round-robin over the workgroups
             char* rs = a.rot + (size_t)l * a.rot_stride;
             AttnArgs aa;
             aa.q = (const uint4*)(rs + a.o_q);
@@ -169,18 +159,10 @@ __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
             }
         } else {
             GemmArgs ga = gemm_args(l, k);
-            gemm_direct_body<EL, TB, D, -1, true>(ga, wg, smem, w, preloaded);
-            preloaded = false;
+            gemm_direct_body<EL, TB, D, -1, true>(ga, wg, smem);
         }
         if (ph + 1 < n_phases) {
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this lane's stores are out
-            if (k != 0) {
-                // the next phase is a GEMM (after QKV comes attention, which needs the registers)
-                const int k2 = (k == 4) ? 0 : k + 1, l2 = (k == 4) ? l + 1 : l;
-                const GemmArgs gn = gemm_args(l2, k2);
-                gemm_direct_prefetch(gn, wg, w);
-                preloaded = true;
-            }
             if (a.tstamp && l == 1 && threadIdx.x == 0) a.tstamp[blockIdx.x * 16 + (stamp_i++)] = wall_clock64();
             if (!grid_barrier(a, ++gen, failed)) return;
             if (a.tstamp && l == 1 && threadIdx.x == 0) a.tstamp[blockIdx.x * 16 + (stamp_i++)] = wall_clock64();

@@ -269,13 +269,15 @@ def test_rejected_calls_change_nothing(fvmod):
 @pytest.mark.parametrize("name", ["tiny", "small-gqa"])
 def test_persistent_kernel_and_per_gemm_path_agree(fvmod, name, monkeypatch):
     """Steps of up to 64 nodes take one launch per GEMM by default; FV_PERSISTENT=1 runs all layers
-    in one persistent kernel.  Both must match the oracle, and each other bit for bit (same
-    split, same summation order)."""
+    in one persistent kernel, whose GEMM phases are the direct-operand kernel's body.  Both must
+    match the oracle, and -- with FV_GEMM=direct on the per-launch side -- each other bit for bit
+    (same split, same summation order)."""
     s, w = SHAPES[name], weights_of(name)
     tol = H.tol_for(s)
     say("persistent-vs-launches", name)
     case = H.planted_case(s, w, 70, 48, [6, 3, 2, 2, 1, 1], 3, seed=2)
     outs = []
+    monkeypatch.setenv("FV_GEMM", "direct")
     for flag in ("1", "0"):
         monkeypatch.setenv("FV_PERSISTENT", flag)
         g = make_gpu(fvmod, s, w, max_seq=160, max_tree=64)
@@ -289,12 +291,14 @@ def test_persistent_kernel_and_per_gemm_path_agree(fvmod, name, monkeypatch):
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
 
 
-@pytest.mark.parametrize("kind", ["wide", "shared"])
+@pytest.mark.parametrize("kind", ["direct", "paired", "wide", "shared"])
 @pytest.mark.parametrize("name", ["tiny", "small-gqa", "small-gqa-f32"])
 def test_alternative_gemm_kernels_match_the_oracle(fvmod, name, kind, monkeypatch):
-    """Up to 64 tokens the GEMMs default to the direct-operand kernel; FV_GEMM selects the
-    four-strips-per-wavefront kernel ("wide") or the LDS-shared-activation kernel ("shared")
-    instead (per-GEMM launches).  Same bar against the oracle for each."""
+    """Up to 64 tokens the GEMMs default to the paired form of the direct-operand kernel wherever the
+    K range is long enough for it (all matrices of small-gqa-f32, O and down of small-gqa, down of
+    tiny) and to the one-strip form elsewhere; FV_GEMM forces the one-strip form ("direct"), the
+    four-strips-per-wavefront kernel ("wide") or the LDS-shared-activation kernel ("shared").  Same bar
+    against the oracle for each."""
     s, w = SHAPES[name], weights_of(name)
     tol = H.tol_for(s)
     say("gemm-kind", kind, name)
