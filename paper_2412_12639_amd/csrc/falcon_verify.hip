@@ -754,6 +754,9 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
         build_split_tables(p, tab);
         if (hipMemcpy(c->arena + p.off_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return fail(FV_E_HIP);
     }
+    for (int i = 0; i < GM_COUNT; ++i)   // the direct kernels split their work with 32-bit arithmetic
+        for (const GemmPlan* q : {&c->lay.gd[i], &c->lay.gp[i]})
+            if ((long long)q->NG * q->NB * (q->G + 1) >= (1LL << 31)) return fail(FV_E_BAD_ARG);
     rc = (cfg->dtype == FV_BF16) ? set_gemm_attrs<BF16>(cfg->head_dim) : set_gemm_attrs<F32>(cfg->head_dim);
     if (rc) return fail(rc);
     *out = c;

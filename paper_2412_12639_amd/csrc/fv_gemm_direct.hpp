@@ -27,6 +27,10 @@
 #pragma once
 // (included from fv_kernels.hpp after GemmArgs, gemm_epilogue and zero_acc)
 
+#ifndef FV_TS
+#define FV_TS(k)   // tuning aid: a stand-alone timing harness defines this to record a time stamp
+#endif
+
 // Shared-memory needs, in floats: one accumulator exchange area [4 wavefronts][tiles][16][64],
 // RMSNorm factors [Tp], reduction scratch [1024], ticket.
 #define FV_DIRECT_SMEM_FLOATS(TB) (4 * (TB) * 1024 + (TB) * 32 + 1024 + 4)
@@ -57,14 +61,19 @@ struct DPlan {
     __device__ __forceinline__ void init(const GemmArgs& a, int wg, int wave_) {
         // computed, not looked up: a table read would put one more memory round trip in front of
         // the first weight load
-        // (32-bit arithmetic: the host only selects these kernels when NG * NB * G < 2^31)
+        // (32-bit arithmetic: the host only selects these kernels when NG * NB * G < 2^31; G is a
+        // power of two whenever there is at least one unit per compute unit, and then a shift)
+        const unsigned G = (unsigned)a.G;
+        const bool pow2 = (G & (G - 1)) == 0;
+        const int sh = 31 - __builtin_clz(G);
+        auto divG = [&](unsigned v) { return pow2 ? (v >> sh) : v / G; };
         if (a.aligned) {   // whole row groups per workgroup: counts differ by at most one
-            u0 = (int)((unsigned)(a.NG * wg) / (unsigned)a.G) * a.NB;
-            u1 = (int)((unsigned)(a.NG * (wg + 1)) / (unsigned)a.G) * a.NB;
+            u0 = (int)divG((unsigned)(a.NG * wg)) * a.NB;
+            u1 = (int)divG((unsigned)(a.NG * (wg + 1))) * a.NB;
         } else {
             const unsigned U = (unsigned)(a.NG * a.NB);
-            u0 = (int)(U * (unsigned)wg / (unsigned)a.G);
-            u1 = (int)(U * (unsigned)(wg + 1) / (unsigned)a.G);
+            u0 = (int)divG(U * (unsigned)wg);
+            u1 = (int)divG(U * (unsigned)(wg + 1));
         }
         NB = a.NB; wave = wave_;
         g0 = u0 / NB;
@@ -129,6 +138,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tl = lane & 31, g = lane >> 5;
     if (wg >= a.G) return;
+    FV_TS(0)
 
     // RMSNorm factor of every token from the [n_ssq][Tp] partial sums of squares.  These loads go out
     // before anything else (L2 hits; the work-split arithmetic below runs while they are in flight),
@@ -156,6 +166,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         }
     }
 
+    FV_TS(1)
     DPlan pl;
     pl.init(a, wg, wave);
     const int nseg = pl.nseg;
@@ -209,6 +220,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
 
     uint4 w[3][FV_FRAGS], x[3][NX];
     enter_slice(0);
+    FV_TS(2)
     // prologue in the loop's own issue order: X(0) W(0) X(1) W(1) X(2) W(2)
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
@@ -217,7 +229,9 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         load_w(w[i]);
         __builtin_amdgcn_sched_barrier(0);
         advance();
+        if (i == 0) { FV_TS(3) }
     }
+    FV_TS(4)
 
     if (with_norm) {
         constexpr int C4 = Tp / 4, SL = 256 / C4;
@@ -313,6 +327,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         advance();                                                                          \
     }
 
+    FV_TS(5)
     for (int s = 0; s < nseg; ++s) {
         int gi, ws, we;
         pl.slice(s, gi, ws, we);
@@ -330,8 +345,10 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         for (int t_ = 0; t_ < NT; ++t_)
 #pragma unroll
             for (int i = 0; i < 16; ++i) my[(t_ * 16 + i) * 64] = acc[t_][i];
+        if (s == 0) { FV_TS(6) }
         finish_segment(s);
     }
+    FV_TS(7)
 #undef FV_DSTAGE
 }
 

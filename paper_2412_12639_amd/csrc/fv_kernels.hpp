@@ -537,12 +537,20 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
     const int kb_lo = nkb * part / a.ks, kb_hi = nkb * (part + 1) / a.ks;   // this workgroup's key blocks
     const int lidx = tl * 2 + g;   // position of this lane's 16 bytes inside a 1 KiB tile
     for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
+        // all K and V tiles of the block are requested before the first is used: one memory round
+        // trip per block instead of two (a workgroup handles only one or two blocks per wavefront)
+        const uint4* kp = kslab + (size_t)kb * NF * 64 + lidx;
+        const uint4* vp = vslab + (size_t)kb * DB * NQ * 64 + lidx;
+        uint4 kt[NF], vt[DB * NQ];
+#pragma unroll
+        for (int fr = 0; fr < NF; ++fr) kt[fr] = kp[fr * 64];
+#pragma unroll
+        for (int j = 0; j < DB * NQ; ++j) vt[j] = vp[j * 64];
         floatx16 s;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[i] = 0.f;
-        const uint4* kp = kslab + (size_t)kb * NF * 64 + lidx;
 #pragma unroll
-        for (int fr = 0; fr < NF; ++fr) s = Tr<EL>::mma(kp[fr * 64], qf[fr], s);
+        for (int fr = 0; fr < NF; ++fr) s = Tr<EL>::mma(kt[fr], qf[fr], s);
 
         float p[16];
         float mx = -1e30f;
@@ -572,13 +580,12 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
         uint4 pb[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q) pb[q] = Tr<EL>::pack(p + q * E);
-        const uint4* vp = vslab + (size_t)kb * DB * NQ * 64 + lidx;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) o[db] = Tr<EL>::mma(vp[(db * NQ + q) * 64], pb[q], o[db]);
+            for (int q = 0; q < NQ; ++q) o[db] = Tr<EL>::mma(vt[db * NQ + q], pb[q], o[db]);
         }
     }
     l_run += __shfl_xor(l_run, 32);
@@ -651,26 +658,32 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
     __syncthreads();
     if (*ticket_lds != a.ks - 1) return;
     if (tid == 0) __hip_atomic_store(&a.tickets[item], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next use
-    // wavefront w combines 32-feature block w (blocks beyond D/32 have no wavefront)
+    // wavefront w combines 32-feature block w (blocks beyond D/32 have no wavefront).  Everything it
+    // needs from the up to eight parts is requested in one go (parts beyond ks re-read part 0 and
+    // get weight zero), so the merge costs one memory round trip.
     const float* base = a.part + (size_t)item * a.ks * PF;
-    float Mx = -1e30f;
-    for (int c = 0; c < a.ks; ++c)
-        Mx = fmaxf(Mx, __hip_atomic_load(base + (size_t)c * PF + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     for (int db = wave; db < DB; db += 4) {
+        float mc[8], lc[8], v[8][16];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const float* cp = base + (size_t)(c < a.ks ? c : 0) * PF;
+            mc[c] = __hip_atomic_load(cp + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            lc[c] = __hip_atomic_load(cp + DB * 1024 + 32 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[c][i] = __hip_atomic_load(cp + (db * 16 + i) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        float Mx = -1e30f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) if (c < a.ks) Mx = fmaxf(Mx, mc[c]);
         float accv[16], ltot = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) accv[i] = 0.f;
-        for (int c = 0; c < a.ks; ++c) {
-            const float* cp = base + (size_t)c * PF;
-            float v[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = __hip_atomic_load(cp + (db * 16 + i) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float mc = __hip_atomic_load(cp + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float lc = __hip_atomic_load(cp + DB * 1024 + 32 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float wc = __expf(mc - Mx);
-            ltot += wc * lc;
+        for (int c = 0; c < 8; ++c) {   // part order
+            const float wc = (c < a.ks) ? __expf(mc[c] - Mx) : 0.f;
+            ltot += wc * lc[c];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) accv[i] += wc * v[i];
+            for (int i = 0; i < 16; ++i) accv[i] += wc * v[c][i];
         }
         const float inv = (ltot > 0.f) ? 1.f / ltot : 0.f;
 #pragma unroll
