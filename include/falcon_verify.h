@@ -155,6 +155,14 @@ int fv_get_argmax(fv_ctx* ctx, int32_t* out, int32_t n_nodes);
 /* Compaction moves of the last verify: src_slot[j] = tree index of path node j,
  * dst_slot[j] = cache slot it was copied to; *count = a + 1.  Capacity >= max_tree. */
 int fv_get_kv_moves(fv_ctx* ctx, int32_t* src_slot, int32_t* dst_slot, int32_t* count);
+/* Features of the accepted path of the last fv_verify_tree, for the next drafting round (section
+ * "Custom-Designed Decoding Tree": the accepted tokens are recorded together with their
+ * features; section "Framework": the drafter consumes the LLM's last-layer features, shifted by
+ * one against the tokens).  Row j, j = 0..accepted_len, is the LM head's input of path node j --
+ * the last layer's output after the final RMSNorm (the paper does not say before or after that
+ * norm; after is what the shared LM head consumes) -- as fp32, row-major [n_rows, hidden].
+ * out: host buffer; n_rows in 1..accepted_len+1, else FV_E_BAD_ARG; nothing is changed. */
+int fv_get_features(fv_ctx* ctx, float* out, int32_t n_rows);
 /* K (after rotation) and V of cache slots [slot0, slot0+n) of one layer, as fp32
  * [n, n_kv_heads, head_dim] each, in logical order. */
 int fv_read_kv(fv_ctx* ctx, int32_t layer, int32_t slot0, int32_t n, float* k_out, float* v_out);

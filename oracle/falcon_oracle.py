@@ -137,9 +137,10 @@ def _kv_head_of(qh, shape):
     return qh * shape.n_kv_heads // shape.n_q_heads
 
 
-def causal_forward(shape, weights, tokens, dtype=np.float64):
+def causal_forward(shape, weights, tokens, dtype=np.float64, return_hidden=False):
     """Logits [n, V] of the decoder over a whole token sequence with a lower-
-    triangular mask, computed from scratch with no cache."""
+    triangular mask, computed from scratch with no cache.  With return_hidden also the
+    LM head's input [n, hidden] (the last layer's output after the final norm)."""
     s = shape
     n = len(tokens)
     x = _up(weights["embed"], dtype)[np.asarray(tokens)]
@@ -162,7 +163,8 @@ def causal_forward(shape, weights, tokens, dtype=np.float64):
         a = silu(linear(xn, W("wg"), dtype)) * linear(xn, W("wu"), dtype)
         x = x + linear(a, W("wd"), dtype)
     xn = rmsnorm(x, weights["g_final"].astype(dtype), s.rms_eps)
-    return linear(xn, weights["lm_head"], dtype)
+    logits = linear(xn, weights["lm_head"], dtype)
+    return (logits, xn) if return_hidden else logits
 
 
 def greedy_decode(shape, weights, tokens, n_new, dtype=np.float64):
@@ -236,6 +238,8 @@ class Oracle:
             a = silu(linear(xn, W("wg"), dt) * post) * (linear(xn, W("wu"), dt) * post)
             x = x + linear(st(a), W("wd"), dt)
         xn, post = self._norm_in(x, self.w["g_final"].astype(dt))
+        # features: what the LM head consumes (the last layer's output after the final norm)
+        self.last_hidden = rmsnorm(x, self.w["g_final"].astype(dt), s.rms_eps)
         return linear(xn, self.w["lm_head"], dt) * post, newK, newV
 
     def _norm_in(self, x, gain):
@@ -290,7 +294,10 @@ class Oracle:
     def verify_tree(self, tokens, parent, depth):
         """One verification step.  Returns a dict with
         logits [T,V], argmax [T], mask [T,4] u64, accepted_len a, accepted_tokens [a],
-        next_token, path [a+1] (tree indices root..best), src_slot / dst_slot [a+1]."""
+        next_token, path [a+1] (tree indices root..best), src_slot / dst_slot [a+1],
+        features [a+1, hidden]: the LM head's input of every path node, recorded with the
+        accepted tokens for the next drafting round (section "Custom-Designed Decoding Tree";
+        reading: after the final norm, i.e. exactly what the shared LM head consumes)."""
         s, L = self.s, self.L
         if self.pending is None:
             raise TreeVerifyError("no prefill")
@@ -326,7 +333,8 @@ class Oracle:
         self.pending = next_token
         return dict(logits=logits, argmax=am, mask=ancestor_mask(parent), accepted_len=a,
                     accepted_tokens=accepted_tokens, next_token=next_token,
-                    path=src, src_slot=src, dst_slot=dst, tree_k=newK, tree_v=newV)
+                    path=src, src_slot=src, dst_slot=dst, tree_k=newK, tree_v=newV,
+                    features=self.last_hidden[src].copy())
 
     def rollback(self, new_len, pending):
         self.L, self.pending = int(new_len), int(pending)

@@ -66,6 +66,7 @@ def load_library():
         "fv_get_logits": [vp, C.POINTER(C.c_float), C.c_int32],
         "fv_get_argmax": [vp, i32p, C.c_int32],
         "fv_get_kv_moves": [vp, i32p, i32p, i32p],
+        "fv_get_features": [vp, C.POINTER(C.c_float), C.c_int32],
         "fv_read_kv": [vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
         "fv_debug_read_activation": [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float)],
         "fv_set_profiling": [vp, C.c_int32],
@@ -237,6 +238,12 @@ class FalconVerifier:
         self._chk(self.lib.fv_get_kv_moves(self.ctx, src.ctypes.data_as(C.POINTER(C.c_int32)),
                                            dst.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(cnt)), "fv_get_kv_moves")
         return src[:cnt.value].copy(), dst[:cnt.value].copy()
+
+    def features(self, n_rows: int):
+        """LM-head inputs (post final norm) of the first n_rows nodes of the accepted path -> [n_rows, hidden] float32."""
+        out = np.zeros((n_rows, self.shape.hidden), dtype=np.float32)
+        self._chk(self.lib.fv_get_features(self.ctx, out.ctypes.data_as(C.POINTER(C.c_float)), n_rows), "fv_get_features")
+        return out
 
     def read_kv(self, layer: int, slot0: int, n: int):
         s = self.shape

@@ -52,7 +52,7 @@ struct Layout {
     size_t off_kvread = 0, off_stage = 0, stage_bytes = 0;
     // persistent step kernel: rotating activation slots (one per layer + 1), barrier words, error flag
     size_t off_rot = 0, rot_stride = 0, o_xa = 0, o_xm = 0, o_xba = 0, o_xbm = 0, o_ssqa = 0, o_ssqm = 0, o_q = 0, o_attn = 0, o_act = 0;
-    size_t off_bar = 0, off_err = 0, off_tstamp = 0, off_apart = 0, off_atick = 0, off_zeros = 0;
+    size_t off_bar = 0, off_err = 0, off_tstamp = 0, off_apart = 0, off_atick = 0, off_zeros = 0, off_feat = 0;
     size_t total = 0;
 };
 
@@ -191,6 +191,7 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     L.off_rope = take((size_t)FV_MAX_TREE * (d / 2) * 8);
     L.off_am = take(FV_MAX_TREE * 4);
     L.off_res = take(sizeof(FvResult));
+    L.off_feat = take((size_t)FV_MAX_TREE * c.hidden * 4);
     L.off_kvread = take((size_t)2 * 64 * kvd * 4);
     size_t st = (size_t)(qd + 2 * kvd) * c.hidden;
     const size_t cands[4] = {(size_t)c.hidden * qd, (size_t)2 * c.ffn * c.hidden, (size_t)c.hidden * c.ffn,
@@ -552,6 +553,14 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             ca.kcache = c->at<void>(ly.off_k); ca.vcache = c->at<void>(ly.off_v); ca.res = c->at<FvResult>(ly.off_res);
             ca.L = L; ca.S_pad = ly.S_pad;
             hipLaunchKernelGGL((k_compact<EL, D>), dim3(cf.n_layers * cf.n_kv_heads), dim3(D), 0, st, ca);
+            // features of the accepted path (what the drafter is given next to the tokens)
+            FeatureArgs fa;
+            fa.res = c->at<FvResult>(ly.off_res);
+            fa.x = persistent ? (const float*)(c->arena + last_slot + ly.o_xa) : c->at<float>(ly.off_x);
+            fa.ssq = persistent ? (const float*)(c->arena + last_slot + ly.o_ssqa) : c->at<float>(ly.off_ssq);
+            fa.gain = c->gain(2 * cf.n_layers); fa.out = c->at<float>(ly.off_feat);
+            fa.h = h; fa.Tp = Tp; fa.inv_h = 1.f / (float)h; fa.eps = cf.rms_eps;
+            hipLaunchKernelGGL(k_features, dim3(T), dim3(256), 0, st, fa);
         }
         HIPCHK(hipGetLastError());
     }
@@ -875,6 +884,12 @@ int fv_get_kv_moves(fv_ctx* c, int32_t* src, int32_t* dst, int32_t* count) {
     const FvResult& r = *c->h_res;
     *count = r.accepted_len + 1;
     for (int j = 0; j <= r.accepted_len; ++j) { src[j] = r.path[j]; dst[j] = c->last_L + j; }
+    return FV_OK;
+}
+
+int fv_get_features(fv_ctx* c, float* out, int32_t n_rows) {
+    if (!c || !out || !c->last_was_verify || n_rows < 1 || n_rows > c->h_res->accepted_len + 1) return FV_E_BAD_ARG;
+    HIPCHK(hipMemcpy(out, c->at<float>(c->lay.off_feat), (size_t)n_rows * c->cfg.hidden * 4, hipMemcpyDeviceToHost));
     return FV_OK;
 }
 

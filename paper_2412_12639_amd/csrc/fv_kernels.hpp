@@ -752,6 +752,37 @@ struct FvResult {
     int32_t accepted_tokens[FV_MAX_TREE];
 };
 
+// Features of the accepted path for the next drafting round: row j = the LM head's input (final
+// RMSNorm of the last layer's output) of path node j, j = 0..accepted_len, fp32 [max_tree][h].
+// One block per possible path position; blocks beyond the path leave at once.
+struct FeatureArgs {
+    const FvResult* res;
+    const float* x;          // residual stream after the last layer, fp32 [h/4][Tp][4]
+    const float* ssq;        // its per-strip sums of squares [h/32][Tp]
+    const float* gain;       // final norm gain [h]
+    float* out;              // [max_tree][h]
+    int h, Tp;
+    float inv_h, eps;
+};
+
+__global__ __launch_bounds__(256) void k_features(FeatureArgs a) {
+    __shared__ float red[256];
+    const int j = blockIdx.x, tid = threadIdx.x;
+    if (j > a.res->accepted_len) return;
+    const int t = a.res->path[j];
+    float s = 0.f;
+    for (int i = tid; i < a.h / 32; i += 256) s += a.ssq[(size_t)i * a.Tp + t];
+    red[tid] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (tid < w) red[tid] += red[tid + w];
+        __syncthreads();
+    }
+    const float rinv = rsqrtf(red[0] * a.inv_h + a.eps);
+    for (int f = tid; f < a.h; f += 256)
+        a.out[(size_t)j * a.h + f] = a.x[((size_t)(f >> 2) * a.Tp + t) * 4 + (f & 3)] * rinv * a.gain[f];
+}
+
 struct ScanArgs {
     const int32_t* tok_in;   // [3][cap]
     int cap, T;

@@ -89,6 +89,10 @@ def check_step(gpu, case, got, tol, n_layers_kv=None):
     assert nxt == res["next_token"]
     src, dst = gpu.kv_moves()
     assert list(src) == list(res["src_slot"]) and list(dst) == list(res["dst_slot"]), "compaction indices"
+    # features of the accepted path (the LM head's input), same relative bar as the logits
+    feat = gpu.features(a + 1).astype(np.float64)
+    ferr = row_rel_err(feat, np.asarray(res["features"], dtype=np.float64))
+    assert ferr.max() <= tol, f"features rel err {ferr.max():.3e} > {tol}"
     return err.max()
 
 

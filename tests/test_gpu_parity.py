@@ -438,3 +438,66 @@ def test_benchmark_configuration_all_layers(fvmod):
     say("7b, 32 layers: oracle prefill + verify on the host ...")
     case = _full_size_case(s, w, 512, 64, [8, 4, 2, 2, 1, 1], 3, seed=0, deep=True)
     _check_full_size(fvmod, s, w, case, 512, 64)
+
+
+@pytest.mark.parametrize("name", ["small-gqa-f32", "small-gqa"])
+def test_multi_step_decoding_with_a_synthetic_drafter_is_lossless(fvmod, name):
+    """Decoding loop: trees from a synthetic drafter that gets a geometric number of tokens right per
+    step; the concatenation of accepted tokens and bonus tokens must be exactly the target's greedy
+    sequence (the oracle's, and the device's own one-token-at-a-time decoding), and every step must
+    accept exactly the number of tokens the drafter got right."""
+    s, w = SHAPES[name], weights_of(name)
+    tol = H.tol_for(s)
+    say("decode-loop", name)
+    N, L0 = 40, 37
+    prefix = fi.gen_prefix(41, L0, s.vocab)   # a prompt whose first greedy tokens have clear margins in bf16 too
+    o_seq = fo.greedy_decode(s, w, list(prefix), N + 1)          # root, then N more tokens
+    g = make_gpu(fvmod, s, w, max_seq=L0 + N + 64, max_tree=32)
+    root = g.prefill(prefix)
+    # where the oracle's own top-2 gap is inside the tolerance nothing can be demanded beyond that point
+    o_chk = fo.Oracle(s, w, max_seq=L0 + N + 8)
+    o_chk.prefill(list(prefix) + [int(t) for t in o_seq[:N]])
+    lg = o_chk.last_logits[L0 - 1:]                               # row j decides o_seq[j]
+    clear = [fo.top2_margin(lg[j]) > 2 * tol * np.max(np.abs(lg[j])) for j in range(N + 1)]
+    n_sure = clear.index(False) if False in clear else N + 1   # o_seq[:n_sure] are beyond doubt
+    say("greedy tokens with a clear margin before the first near-tie:", n_sure, "of", N + 1)
+    if s.dtype == "f32":
+        assert n_sure == N + 1
+    if n_sure == 0:
+        pytest.skip("the very first greedy token is a near-tie at this precision")
+    assert root == o_seq[0]
+    # plain decoding on the device, one token per step
+    p1, d1 = fi.chain_tree(1)
+    ar, tk = [], root
+    for _ in range(N):
+        a, acc, tk = g.verify_tree([tk], p1, d1)
+        assert a == 0 and len(acc) == 0
+        ar.append(tk)
+    assert ar[:n_sure - 1] == [int(t) for t in o_seq[1:n_sure]]
+    # the same tokens through tree verification; the drafter is fed the DEVICE's greedy sequence, so
+    # that past a near-tie (where device and oracle may part ways) the loop is still checked against
+    # the device's own one-token-at-a-time decoding
+    g.rollback(L0, root)
+    emitted, tk, step, accepted = [], root, 0, []
+    while len(emitted) < N - 6:
+        future = ar[len(emitted):]
+        tokens, parent, depth, n_ok = fi.draft_tree(500 + step, tk, future, 24, [3, 3, 2, 2, 1], 0.75, s.vocab)
+        a, acc, nxt = g.verify_tree(tokens, parent, depth)
+        sure = len(emitted) + n_ok + 1 <= n_sure - 1
+        if sure:
+            assert a == n_ok, f"step {step}: accepted {a}, drafter got {n_ok} right"
+        emitted += list(acc) + [nxt]
+        accepted.append(a)
+        tk = nxt
+        step += 1
+        assert g.state() == (L0 + len(emitted), tk)
+        if emitted != ar[:len(emitted)]:
+            # only a near-tie may make tree verification and single-token decoding disagree
+            k = next(i for i in range(len(emitted)) if emitted[i] != ar[i])
+            assert k + 1 >= n_sure, f"token {k} differs although its margin is clear"
+            say("sequences part at token", k, "(near-tie): stop")
+            break
+    k = min(len(emitted), n_sure - 1)
+    assert emitted[:k] == [int(t) for t in o_seq[1:1 + k]]
+    say("steps", step, "tokens", len(emitted), "mean accepted length", float(np.mean(accepted)))
+    g.close()

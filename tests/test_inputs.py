@@ -81,3 +81,21 @@ def test_step_bytes_headline():
     s = fi.SHAPES["7b"]
     assert s.weight_params() * 2 == 13_214_154_752
     assert abs(s.step_bytes(512, 64) / 1e9 - 13.52) < 0.01
+
+
+def test_synthetic_drafter_plants_the_drawn_number_of_greedy_tokens():
+    future = [5, 9, 2, 7, 7, 1, 3, 8]
+    lens = []
+    for seed in range(200):
+        tok, parent, depth, n_ok = fi.draft_tree(seed, 4, future, 24, [3, 3, 2, 2, 1], 0.75, 50)
+        assert tok[0] == 4 and len(tok) == 24 and all(parent[i] < i for i in range(1, 24))
+        # walk the greedy path through the tree: exactly n_ok tokens match, then none
+        node, k = 0, 0
+        while k < len(future):
+            nxt = [j for j in range(1, 24) if parent[j] == node and tok[j] == future[k]]
+            if not nxt:
+                break
+            node, k = nxt[0], k + 1
+        assert k == n_ok and n_ok <= 5
+        lens.append(n_ok)
+    assert 2.0 < np.mean(lens) < 3.2   # geometric with p = 0.75 capped at depth 5: mean about 2.3-2.6

@@ -45,9 +45,12 @@ def test_causal_forward_matches_library_llama(hq, hkv):
     assert not [k for k in missing.missing_keys if "rotary" not in k]
     toks = fi.gen_prefix(2, 23, s.vocab)
     with torch.no_grad():
-        ref = m(torch.from_numpy(toks.astype(np.int64))[None]).logits[0].numpy()
-    got = fo.causal_forward(s, w, toks)
+        out = m(torch.from_numpy(toks.astype(np.int64))[None], output_hidden_states=True)
+        ref = out.logits[0].numpy()
+        ref_hidden = out.hidden_states[-1][0].numpy()   # the library's last hidden state: after its final norm
+    got, hidden = fo.causal_forward(s, w, toks, return_hidden=True)
     assert got.shape == ref.shape
+    assert np.max(np.abs(hidden - ref_hidden)) / np.max(np.abs(ref_hidden)) < 1e-6
     # the library builds its rotary tables in fp32, which caps the agreement near 1e-7
     assert np.max(np.abs(got - ref)) < 1e-6 * np.max(np.abs(ref))
 
@@ -424,3 +427,20 @@ def test_storage_argument_is_checked(tiny):
     s, w, prefix = tiny
     with pytest.raises(ValueError):
         fo.Oracle(s, w, max_seq=80, storage="fp8")
+
+
+def test_features_are_the_lm_head_input(small):
+    """The features returned with the accepted tokens: multiplying them by the LM head gives the
+    path nodes' logits back (closed form), and they equal the final hidden state of a from-scratch
+    causal forward over prefix ++ root path (brute force)."""
+    s, w, prefix = small
+    o, root, greedy, parent, depth, planted, tok = _planted_tree(s, w, prefix, 0, 16, [4, 2, 1, 1], 3)
+    r = o.verify_tree(tok, parent, depth)
+    f = r["features"]
+    assert f.shape == (r["accepted_len"] + 1, s.hidden) and r["accepted_len"] == 3
+    back = f @ fo._up(w["lm_head"], np.float64).T
+    assert np.max(np.abs(back - r["logits"][r["path"]])) < 1e-10
+    for j, node in enumerate(r["path"]):
+        seq = list(prefix) + [int(tok[k]) for k in fo.root_path(parent, int(node))]
+        _, hid = fo.causal_forward(s, w, seq, return_hidden=True)
+        assert np.max(np.abs(hid[-1] - f[j])) < 1e-10 * np.max(np.abs(hid[-1]))
