@@ -87,6 +87,57 @@ def cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root, sample
     }
 
 
+def decode_loop(fi, gpu, shape, L, root, n_nodes, branching, n_tokens, p_accept, seed):
+    """Context for the paper's headline (wall-time speed-up of lossless speculative decoding over plain
+    decoding): the same n_tokens greedy tokens produced (a) one per step and (b) by tree verification of
+    trees from a synthetic drafter that gets a geometric number of tokens right per step.  The drafter's
+    own cost is NOT included (it is outside this build), so the ratio is an upper bound of an end-to-end
+    speed-up at that acceptance length; the emitted sequences must be identical (losslessness)."""
+    p1, d1 = fi.chain_tree(1)
+    gpu.rollback(L, root)
+    ar, tk = [], root
+    t0 = time.perf_counter()
+    for _ in range(n_tokens):
+        _, _, tk = gpu.verify_tree([tk], p1, d1)
+        ar.append(tk)
+    t_ar = time.perf_counter() - t0
+    gpu.rollback(L, root)
+    emitted, tk, step, acc_lens, resyncs = [], root, 0, [], 0
+    t_spec = 0.0
+    while len(emitted) < n_tokens - len(branching) - 1:
+        tokens, parent, depth, n_ok = fi.draft_tree(seed + 900 + step, tk, ar[len(emitted):], n_nodes, branching, p_accept, shape.vocab)
+        t0 = time.perf_counter()
+        a, acc, nxt = gpu.verify_tree(tokens, parent, depth)
+        t_spec += time.perf_counter() - t0
+        emitted += list(acc) + [nxt]
+        acc_lens.append(a)
+        tk = nxt
+        step += 1
+        if emitted != ar[:len(emitted)]:
+            # The two launch configurations (1 row vs n_nodes rows) round differently, and at 32 bf16 layers
+            # of a random-weight model a top-2 near-tie flips easily: both tokens are valid greedy choices
+            # at this precision.  Count it, and give the drafter the single-token continuation from HERE.
+            resyncs += 1
+            cur = len(emitted)
+            t1 = tk
+            tail = []
+            for _ in range(n_tokens - cur):
+                _, _, t1 = gpu.verify_tree([t1], p1, d1)
+                tail.append(t1)
+            gpu.rollback(L + cur, tk)
+            ar = emitted + tail
+    gpu.rollback(L, root)
+    return {
+        "tokens": len(emitted), "steps": step, "mean_accepted_len": float(np.mean(acc_lens)) if acc_lens else 0.0,
+        "near_tie_disagreements_with_single_token_decoding": resyncs,
+        "single_token_ms_per_token": t_ar / n_tokens * 1e3,
+        "tree_verify_ms_per_token": t_spec / max(1, len(emitted)) * 1e3,
+        "speedup_without_drafting_cost": (t_ar / n_tokens) / (t_spec / max(1, len(emitted))),
+        "note": "synthetic drafter (per-token acceptance %.2f), drafting cost excluded; the paper reports 2.91x-3.51x "
+                "end to end with its own drafter on an H800 server" % p_accept,
+    }
+
+
 def measured_traffic(kname, args, shape):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
     (profiles/traffic_*.md: FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), if one
@@ -115,6 +166,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers in the oracle's CPU-baseline sample (0 = skip)")
     ap.add_argument("--profile-steps", type=int, default=10)
+    ap.add_argument("--loop-tokens", type=int, default=48,
+                    help="tokens of the multi-step decoding comparison (tree verification with a synthetic drafter "
+                         "vs one token per step); 0 = skip")
+    ap.add_argument("--loop-p", type=float, default=0.8, help="per-token acceptance probability of the synthetic drafter")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run three device-to-device copies of this many MiB (a kernel of known HBM traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -200,7 +255,7 @@ def main():
         # step stream all weights once).  Events around every single launch open gaps that inflate
         # a per-launch figure, so its time is taken from the TIMED region instead: the step's device
         # time between its two events, minus the attention and small-kernel time of the profiling pass.
-        kname = "k_gemm_direct (weight-streaming skinny GEMM, all five matrices of the step)"
+        kname = "k_gemm_paired (weight-streaming skinny GEMM, all five matrices of the step)"
         n_launch = ph["gemm"][1] / args.profile_steps
         other_ms = (ph["attn"][0] + ph["other"][0] + ph["fixup"][0]) / args.profile_steps
         ms_per_launch = (float(np.median(dev_ms)) - other_ms) / n_launch
@@ -233,6 +288,8 @@ def main():
                      "launches_per_step": n_launch},
         "phase_ms_per_step": {k: v[0] / args.profile_steps for k, v in ph.items()},
     }
+    if args.loop_tokens > 0:
+        out["decode_loop"] = decode_loop(fi, gpu, shape, L, root, T, branching, args.loop_tokens, args.loop_p, args.seed)
     traffic = measured_traffic(kname, args, shape)
     if traffic is not None:
         out["roofline"]["traffic"] = traffic
