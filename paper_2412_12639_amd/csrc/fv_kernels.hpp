@@ -236,13 +236,14 @@ __device__ __forceinline__ void gemm_compute(const uint4 (&w)[FV_FRAGS], const u
                                              floatx16 (&acc)[TB], int lane) {
     constexpr int Tp = TB * 32;
     const int t = lane & 31, g = lane >> 5;
+    const uint4* xb = xl + g * Tp + t;
 #pragma unroll
     for (int f = 0; f < FV_FRAGS; ++f) {
+        uint4 b[TB];   // all B tiles of the fragment first, so the LDS reads overlap the MFMAs before them
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) {
-            const uint4 b = xl[(2 * f + g) * Tp + tb * 32 + t];
-            acc[tb] = Tr<EL>::mma(w[f], b, acc[tb]);
-        }
+        for (int tb = 0; tb < TB; ++tb) b[tb] = xb[2 * f * Tp + tb * 32];
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[tb] = Tr<EL>::mma(w[f], b[tb], acc[tb]);
     }
 }
 
@@ -364,29 +365,68 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     if ((int)blockIdx.x >= a.G) return;
 
-    // This workgroup's units [u0, u1) of the (row group, K batch) space, as ONE software-pipelined
-    // stream: the weight tiles of unit u+2 and the activation chunk of unit u+1 are in flight
-    // while unit u is multiplied, across row-group boundaries too.  Loads past the end of the
-    // range are clamped to the last unit (an L2 hit) instead of being branched around, so that
-    // the outstanding-load counts the waits are computed from stay exact.
+    // This workgroup's units [u0, u1) of the (row group, K batch) space are one software-pipelined
+    // stream: the weight tiles and the activation chunk of stage k+2 are requested while stage k is
+    // multiplied (weights into the third register set, the chunk into staging registers that go to
+    // the other LDS buffer one stage later), across row-group boundaries too.  Every segment (the
+    // part of the range inside one row group) is padded to whole rounds of three stages; a padded
+    // stage loads zeros as its activation chunk (and one weight line, finite), so the loop body has
+    // no conditional, the accumulators stay in the accumulation registers, and the number of loads
+    // per stage -- which the wait counts are computed from -- is fixed.
     const long long U = (long long)a.NG * a.NB;   // computed, not looked up: no extra round trip before the first load
     const int u0 = (int)(U * blockIdx.x / a.G);
     const int u1 = (int)(U * (blockIdx.x + 1) / a.G);
+    const int g0 = u0 / a.NB;
+    int nseg = 1;
+    for (int e_ = (g0 + 1) * a.NB; e_ < u1; e_ += a.NB) ++nseg;
+    auto segment = [&](int sgm, int& gi, int& b0, int& nb) {
+        gi = g0 + sgm;
+        b0 = (sgm == 0) ? u0 - g0 * a.NB : 0;
+        const int rem = u1 - gi * a.NB;
+        nb = (rem < a.NB ? rem : a.NB) - b0;
+    };
     const uint4* __restrict__ wbase = a.Wt + (size_t)wave * a.NB * (FV_FRAGS * 64) + lane;
     const size_t group_stride = (size_t)R * a.NB * (FV_FRAGS * 64);
-    const uint4* __restrict__ xbase = a.X + tid;
-    const int g0 = u0 / a.NB;
+    const uint4* const zeros = a.zeros;
 
-    // prefetch position (row group, batch) kept incrementally; it stops at the last unit of the range
-    int pu = u0, pg = g0, pb = u0 - g0 * a.NB;
-    auto p_next = [&]() { if (pu + 1 < u1) { ++pu; if (++pb == a.NB) { pb = 0; ++pg; } } };
-    auto w_ptr = [&]() { return wbase + pg * group_stride + (size_t)pb * (FV_FRAGS * 64); };
-    auto x_ptr = [&]() { return xbase + (size_t)pb * CV; };
+    // request position: segment rs, padded stage rj of rn3 (rn real ones), this thread's addresses
+    int rs = 0, rj = 0, rn = 0, rn3 = 0;
+    const uint4* wp = a.Wt;
+    const uint4* xp = zeros;
+    auto enter = [&](int sgm) {
+        rs = sgm; rj = 0; rn = 0; rn3 = 0; wp = a.Wt; xp = zeros;
+        if (rs < nseg) {
+            int gi, b0, nb;
+            segment(rs, gi, b0, nb);
+            rn = nb; rn3 = (nb + 2) / 3 * 3;
+            wp = wbase + (size_t)gi * group_stride + (size_t)b0 * (FV_FRAGS * 64);
+            xp = a.X + (size_t)b0 * CV + tid;
+        }
+    };
+    auto advance = [&]() {
+        ++rj; wp += FV_FRAGS * 64; xp += CV;
+        if (rj >= rn3) enter(rs + 1);
+    };
+    auto load_w = [&](uint4 (&dst)[FV_FRAGS]) {
+        const bool live = rj < rn;
+        const uint4* pw = live ? wp : a.Wt;
+        const int st = live ? 64 : 0;
+#pragma unroll
+        for (int f = 0; f < FV_FRAGS; ++f) dst[f] = pw[f * st];
+    };
+    auto load_x = [&](u32x4 (&dst)[XV]) {
+        const bool live = rj < rn;
+        const uint4* px = live ? xp : zeros;
+        const int st = live ? 64 * R : 0;
+#pragma unroll
+        for (int v = 0; v < XV; ++v) dst[v] = *(const u32x4*)(px + v * st);
+    };
 
     uint4 w[3][FV_FRAGS];
     u32x4 xr[XV];
-    // prologue: W(u0) first, so that it is in flight during the statistics below
-    ld_vec<FV_FRAGS, 64>(w[0], w_ptr());
+    enter(0);
+    // prologue: W(0) first, so that it is in flight during the statistics below
+    load_w(w[0]);
     if constexpr (EPI != EPI_RESID) {
         // RMSNorm factor of every token, while the first weight tiles are in flight.  The
         // [n_ssq][Tp] partial sums of squares are read as float4 (4 tokens) with eight
@@ -415,57 +455,47 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
             rinv_lds[tid] = rsqrtf(tot * a.inv_h + a.eps);
         }
     }
-    // X(u0) -> LDS[0]; then X(u0+1) and W(u0+1) are issued in the same order as inside the loop
+    // X(0) -> LDS[0]; then X(1) and W(1) are issued in the same order as inside the loop
     // (activation chunk before weight tiles), so the loop's wait counts hold from the first stage
-    ld_x<XV, 64 * R>(xr, x_ptr());
+    load_x(xr);
     st_lds<XV, 64 * R>(lds + tid, xr);
     __builtin_amdgcn_sched_barrier(0);
-    p_next();   // unit u0 + 1
-    ld_x<XV, 64 * R>(xr, x_ptr());
+    advance();   // stage 1
+    load_x(xr);
     __builtin_amdgcn_sched_barrier(0);
-    ld_vec<FV_FRAGS, 64>(w[1], w_ptr());
+    load_w(w[1]);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
 
-    floatx16 acc[TB];
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[tb][i] = 0.f;
-    int seg = 0, seg_batches = 0;
-    int gi = g0, b = u0 - g0 * a.NB;
-
-    // one pipeline stage for unit u with weight register set S; the loads it issues go to set S2
-#define FV_STAGE(S, S2, u)                                                                              \
+    int par = 0;   // LDS buffer that holds the current stage's chunk
+    // one pipeline stage with weight register set S; the loads it issues (stage + 2) go to set S2
+#define FV_STAGE(S, S2)                                                                                 \
     {                                                                                                   \
-        const int u_ = (u);                                                                             \
-        const int par_ = (u_ - u0) & 1;                                                                 \
-        if (u_ < u1) gemm_compute<EL, TB>(w[S], lds + par_ * CV, acc, lane);                            \
+        gemm_compute<EL, TB>(w[S], lds + par * CV, acc, lane);                                          \
         __builtin_amdgcn_sched_barrier(0);                                                              \
-        st_lds<XV, 64 * R>(lds + (par_ ^ 1) * CV + tid, xr);                                            \
+        st_lds<XV, 64 * R>(lds + (par ^ 1) * CV + tid, xr);                                             \
         __builtin_amdgcn_sched_barrier(0);                                                              \
-        p_next(); /* unit u + 2 (or the last one) */                                                    \
-        ld_x<XV, 64 * R>(xr, x_ptr());                                                                  \
+        advance();                                                                                      \
+        load_x(xr);                                                                                     \
         __builtin_amdgcn_sched_barrier(0);                                                              \
-        ld_vec<FV_FRAGS, 64>(w[S2], w_ptr());                                                           \
+        load_w(w[S2]);                                                                                  \
         __builtin_amdgcn_sched_barrier(0);                                                              \
         __syncthreads();                                                                                \
-        if (u_ < u1) {                                                                                  \
-            ++seg_batches;                                                                              \
-            if (b == a.NB - 1 || u_ == u1 - 1) {                                                        \
-                gemm_flush<EL, TB, D, EPI>(a, acc, gi, seg_batches, seg, rinv_lds, &ticket_lds);        \
-                zero_acc<TB>(acc);                                                                      \
-                ++seg; seg_batches = 0; ++gi; b = 0;                                                    \
-            } else {                                                                                    \
-                ++b;                                                                                    \
-            }                                                                                           \
-        }                                                                                               \
+        par ^= 1;                                                                                       \
     }
 
-    for (int u = u0; u < u1; u += 3) {
-        FV_STAGE(0, 2, u)
-        FV_STAGE(1, 0, u + 1)
-        FV_STAGE(2, 1, u + 2)
+    for (int sgm = 0; sgm < nseg; ++sgm) {
+        int gi, b0, nb;
+        segment(sgm, gi, b0, nb);
+        const int rounds = (nb + 2) / 3;
+        floatx16 acc[TB];
+        zero_acc<TB>(acc);
+        for (int r = 0; r < rounds; ++r) {
+            FV_STAGE(0, 2)
+            FV_STAGE(1, 0)
+            FV_STAGE(2, 1)
+        }
+        gemm_flush<EL, TB, D, EPI>(a, acc, gi, nb, sgm, rinv_lds, &ticket_lds);
     }
 #undef FV_STAGE
 }
