@@ -1,8 +1,7 @@
 // Skinny GEMM for up to 64 tokens, "wide" form, for the matrices with many output rows (QKV,
-// gate/up, LM head).  Measured on this part, a compute unit receives at most ~16 bytes per clock
-// from global memory whatever the source (HBM, L2 or L1), i.e. ~9.5 TB/s over the chip, while the
-// HBM stream alone wants ~6.  Activation tiles therefore may cost at most about half as many bytes
-// as the weight tiles they meet.  Here every wavefront owns FOUR 32-row strips (a "super-strip")
+// gate/up, LM head).  An experiment kept as an option (FV_GEMM=wide): the vector-load path of a
+// compute unit is a shared resource between weight tiles (HBM) and activation tiles (L2/L1), so
+// the fewer activation bytes per weight byte the better.  Here every wavefront owns FOUR 32-row strips (a "super-strip")
 // and one quarter of their K range: an activation tile (2 KiB at 64 tokens) is loaded once and
 // meets four weight tiles (4 KiB), all in registers -- no LDS and no barrier in the stream.
 //
@@ -12,10 +11,11 @@
 // that covers the whole K range goes to the epilogue, otherwise partial tiles + ticket, and the
 // last arriver sums in ascending workgroup order (deterministic).
 //
-// A wavefront moves 32 KiB of weights per batch, which at full HBM rate takes several
-// microseconds: a strip's register set is refilled with the next batch's tile right after it has
-// been multiplied (four sets, one per strip), and the single activation set is refilled after the
-// batch's last product; the latency this exposes is well below the batch's share of HBM time.
+// A wavefront moves 32 KiB of weights per batch: a strip's register set is refilled with the next
+// batch's tile right after it has been multiplied (four sets, one per strip), and the single
+// activation set is refilled after the batch's last product.  Only one batch ahead fits the
+// register file, which exposes two memory latencies per batch; measured, this form loses to the
+// paired form of the direct kernel on every matrix but the LM head.
 #pragma once
 // (included from fv_kernels.hpp after fv_gemm_direct.hpp)
 
