@@ -355,8 +355,10 @@ int set_gemm_attrs_d() {
     if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_SWIGLU>();
     if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_LOGITS>();
     if (!rc) {
-        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 1, D>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(1, D) * 4));
-        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 2, D>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(2, D) * 4));
+        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 1, D, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(1, D) * 4));
+        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 2, D, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(2, D) * 4));
+        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 1, D, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(1, D) * 4));
+        HIPCHK(hipFuncSetAttribute((const void*)k_step_persistent<EL, 2, D, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PERSIST_SMEM_FLOATS(2, D) * 4));
     }
     return rc;
 }
@@ -400,16 +402,20 @@ int launch_persistent(fv_ctx* c, int T, int Tp, int L) {
     pa.bar = c->at<unsigned>(ly.off_bar); pa.gen0 = c->bar_gen; pa.err = c->at<int>(ly.off_err);
     pa.tstamp = getenv("FV_PERSIST_TIMING") ? c->at<long long>(ly.off_tstamp) : nullptr;
     pa.ts_phase = getenv("FV_PERSIST_TIMING") ? atoi(getenv("FV_PERSIST_TIMING")) : 0;
+    // paired form in the GEMM phases if every layer matrix allows it and it is the selected kind
+    bool paired = true;
+    for (int i = 0; i < 4; ++i) paired = paired && c->kind[i] == GEMM_PAIRED;
     int grid = 1;
     for (int i = 0; i < 4; ++i) {
-        const GemmPlan& p = ly.gd[i];
+        const GemmPlan& p = paired ? ly.gp[i] : ly.gd[i];
         pa.g[i].NG = p.NG; pa.g[i].NB = p.NB; pa.g[i].G = p.G; pa.g[i].segmax = p.segmax; pa.g[i].n_strips = p.n_strips; pa.g[i].aligned = p.aligned;
         pa.g[i].tab = c->at<int>(p.off_tab);
         if (p.G > grid) grid = p.G;
     }
     if (grid > 256) return 1;   // the barrier polls one slot per thread of workgroup 0
     void* args[] = {&pa};
-    const void* fn = (Tp == 32) ? (const void*)k_step_persistent<EL, 1, D> : (const void*)k_step_persistent<EL, 2, D>;
+    const void* fn = paired ? ((Tp == 32) ? (const void*)k_step_persistent<EL, 1, D, 2> : (const void*)k_step_persistent<EL, 2, D, 2>)
+                            : ((Tp == 32) ? (const void*)k_step_persistent<EL, 1, D, 1> : (const void*)k_step_persistent<EL, 2, D, 1>);
     const unsigned smem = (Tp == 32 ? FV_PERSIST_SMEM_FLOATS(1, D) : FV_PERSIST_SMEM_FLOATS(2, D)) * 4;
     hipError_t e = hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), args, smem, c->stream);
     if (e != hipSuccess) { (void)hipGetLastError(); return 1; }

@@ -122,8 +122,50 @@ struct DReq {
 // EPI >= 0: epilogue fixed at compile time; EPI = -1: taken from a.epi at run time (the persistent
 // step kernel runs all its GEMMs through one copy of this body).  COH: outputs are read by other
 // workgroups of the same launch (see st_u64).  `wg` is this workgroup's index in the split.
+// Requests the weight tiles of the first three stages of this wavefront's stream into `w`: exactly
+// what gemm_direct_body's prologue would request (same split, same slices, same padding).
+template <int RS>
+__device__ __forceinline__ void gemm_direct_prefetch(const GemmArgs& a, int wg, uint4 (&w)[3][FV_FRAGS]) {
+    constexpr int SF = FV_FRAGS / RS;
+    if (wg >= a.G) return;
+    const int lane = threadIdx.x & 63;
+    DPlan pl;
+    pl.init(a, wg, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+    int sl = 0, j = 0, n = 0, n3 = 0;
+    const uint4* wp = a.zeros;
+    auto enter = [&](int s0) {
+        sl = s0; j = 0; n = 0; n3 = 0; wp = a.zeros;
+        while (sl < pl.nseg) {
+            int gi, ws, we;
+            pl.slice(sl, gi, ws, we);
+            if (we > ws) {
+                n = we - ws; n3 = (n + 2) / 3 * 3;
+                wp = a.Wt + ((size_t)gi * RS * a.NB + ws) * (SF * 64) + lane;
+                return;
+            }
+            ++sl;
+        }
+    };
+    enter(0);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const bool live = j < n;
+        const uint4* p = live ? wp : a.zeros;
+        const size_t rstride = live ? (size_t)a.NB * (SF * 64) : 0;
+#pragma unroll
+        for (int r = 0; r < RS; ++r)
+#pragma unroll
+            for (int f = 0; f < SF; ++f) w[i][r * SF + f] = (p + r * rstride)[f * 64];
+        ++j; wp += SF * 64;
+        if (j >= n3) enter(sl + 1);
+    }
+}
+
+// `w` are the three weight register sets; if `preloaded`, gemm_direct_prefetch has already requested
+// the first three stages into them (the persistent kernel does that ahead of the grid barrier that
+// ends the previous phase: weights do not depend on activations).
 template <typename EL, int TB, int D, int EPI, bool COH, int RS = 1>
-__device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, float* smem) {
+__device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, float* smem, uint4 (&w)[3][FV_FRAGS], bool preloaded) {
     constexpr int Tp = TB * 32;
     constexpr int SF = FV_FRAGS / RS;            // fragments per stage
     constexpr int NX = SF * TB;                  // activation tiles per stage
@@ -218,7 +260,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         if (rq.j >= rq.n3) enter_slice(rq.s + 1);   // also taken, harmlessly, once the stream has ended
     };
 
-    uint4 w[3][FV_FRAGS], x[3][NX];
+    uint4 x[3][NX];
     enter_slice(0);
     FV_TS(2)
     // prologue in the loop's own issue order: X(0) W(0) X(1) W(1) X(2) W(2)
@@ -226,7 +268,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     for (int i = 0; i < 3; ++i) {
         load_x(x[i]);
         __builtin_amdgcn_sched_barrier(0);
-        load_w(w[i]);
+        if (!preloaded) load_w(w[i]);
         __builtin_amdgcn_sched_barrier(0);
         advance();
         if (i == 0) { FV_TS(3) }
@@ -355,12 +397,14 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
 template <typename EL, int TB, int D, int EPI>
 __global__ __launch_bounds__(256, 1) void k_gemm_direct(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem_dyn[];   // FV_DIRECT_SMEM_FLOATS(TB) floats
-    gemm_direct_body<EL, TB, D, EPI, false>(a, blockIdx.x, smem_dyn);
+    uint4 w[3][FV_FRAGS];
+    gemm_direct_body<EL, TB, D, EPI, false>(a, blockIdx.x, smem_dyn, w, false);
 }
 
 // Two strips per wavefront, half-batch stages.  a.NG counts 64-row groups, a.NB half batches.
 template <typename EL, int TB, int D, int EPI>
 __global__ __launch_bounds__(256, 1) void k_gemm_paired(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem_dyn[];   // FV_PAIRED_SMEM_FLOATS(TB) floats
-    gemm_direct_body<EL, TB, D, EPI, false, 2>(a, blockIdx.x, smem_dyn);
+    uint4 w[3][FV_FRAGS];
+    gemm_direct_body<EL, TB, D, EPI, false, 2>(a, blockIdx.x, smem_dyn, w, false);
 }

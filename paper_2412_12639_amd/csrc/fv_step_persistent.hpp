@@ -89,9 +89,11 @@ __device__ __forceinline__ bool grid_barrier(const PersistArgs& a, unsigned gen,
 }
 
 #define FV_PERSIST_SMEM_FLOATS(TB, D) \
-    (FV_DIRECT_SMEM_FLOATS(TB) > FV_ATTN_SMEM_FLOATS(D) ? FV_DIRECT_SMEM_FLOATS(TB) : FV_ATTN_SMEM_FLOATS(D))
+    (FV_PAIRED_SMEM_FLOATS(TB) > FV_ATTN_SMEM_FLOATS(D) ? FV_PAIRED_SMEM_FLOATS(TB) : FV_ATTN_SMEM_FLOATS(D))
 
-template <typename EL, int TB, int D>
+// RS: strips per wavefront in the GEMM phases (1: direct form, 2: paired form; the host passes the
+// matching split plans).
+template <typename EL, int TB, int D, int RS>
 __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem[];   // FV_PERSIST_SMEM_FLOATS(TB, D) floats
     const int wg = blockIdx.x;
@@ -139,11 +141,21 @@ __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
 
     // Phases 0..4 of layer l: QKV, attention, O, gate/up, down.  One loop, so that the GEMM body
     // (the bulk of the code) is instantiated once and the kernel stays inside the instruction cache.
+    // The weight tiles of a GEMM phase's first three stages are requested BEFORE the barrier that ends
+    // the previous phase (weights do not depend on activations), so HBM works through the barrier.
+    // Not across the attention phase, which needs the registers.
+    uint4 w[3][FV_FRAGS];
+    bool preloaded = false;
     const int n_phases = 5 * a.n_layers;
     for (int ph = 0; ph < n_phases; ++ph) {
         const int l = ph / 5, k = ph - 5 * l;
         if (k == 1) {
-            // tree attention: (head, 32-node block, key part) units round-robin over the workgroups
+            // tree attention: (head, 32-node block, key part) units round-robin over the workgroups.
+            // (Nothing is prefetched across this phase: say so, or the weight registers stay reserved.)
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+#pragma unroll
+                for (int f = 0; f < FV_FRAGS; ++f) w[i][f] = make_uint4(0u, 0u, 0u, 0u);
             char* rs = a.rot + (size_t)l * a.rot_stride;
             AttnArgs aa;
             aa.q = (const uint4*)(rs + a.o_q);
@@ -159,10 +171,17 @@ __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
             }
         } else {
             GemmArgs ga = gemm_args(l, k);
-            gemm_direct_body<EL, TB, D, -1, true>(ga, wg, smem);
+            gemm_direct_body<EL, TB, D, -1, true, RS>(ga, wg, smem, w, preloaded);
+            preloaded = false;
         }
         if (ph + 1 < n_phases) {
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this lane's stores are out
+            if (k != 0) {   // the next phase is a GEMM
+                const int k2 = (k == 4) ? 0 : k + 1, l2 = (k == 4) ? l + 1 : l;
+                const GemmArgs gn = gemm_args(l2, k2);
+                gemm_direct_prefetch<RS>(gn, wg, w);
+                preloaded = true;
+            }
             if (a.tstamp && l == 1 && threadIdx.x == 0) a.tstamp[blockIdx.x * 16 + (stamp_i++)] = wall_clock64();
             if (!grid_barrier(a, ++gen, failed)) return;
             if (a.tstamp && l == 1 && threadIdx.x == 0) a.tstamp[blockIdx.x * 16 + (stamp_i++)] = wall_clock64();

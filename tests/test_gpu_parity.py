@@ -266,18 +266,19 @@ def test_rejected_calls_change_nothing(fvmod):
     g.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "small-gqa"])
-def test_persistent_kernel_and_per_gemm_path_agree(fvmod, name, monkeypatch):
+@pytest.mark.parametrize("name,gemm", [("tiny", "direct"), ("small-gqa", "direct"), ("small-gqa-f32", "paired")])
+def test_persistent_kernel_and_per_gemm_path_agree(fvmod, name, gemm, monkeypatch):
     """Steps of up to 64 nodes take one launch per GEMM by default; FV_PERSISTENT=1 runs all layers
-    in one persistent kernel, whose GEMM phases are the direct-operand kernel's body.  Both must
-    match the oracle, and -- with FV_GEMM=direct on the per-launch side -- each other bit for bit
-    (same split, same summation order)."""
+    in one persistent kernel, whose GEMM phases are the direct-operand kernel's body (paired form if
+    every layer matrix takes it, as on small-gqa-f32; else one strip per wavefront).  Both must match
+    the oracle, and -- with the same GEMM form on the per-launch side -- each other bit for bit (same
+    split, same summation order)."""
     s, w = SHAPES[name], weights_of(name)
     tol = H.tol_for(s)
-    say("persistent-vs-launches", name)
+    say("persistent-vs-launches", name, gemm)
     case = H.planted_case(s, w, 70, 48, [6, 3, 2, 2, 1, 1], 3, seed=2)
     outs = []
-    monkeypatch.setenv("FV_GEMM", "direct")
+    monkeypatch.setenv("FV_GEMM", gemm)
     for flag in ("1", "0"):
         monkeypatch.setenv("FV_PERSISTENT", flag)
         g = make_gpu(fvmod, s, w, max_seq=160, max_tree=64)
