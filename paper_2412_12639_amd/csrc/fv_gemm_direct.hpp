@@ -38,13 +38,13 @@
 
 template <typename EL, int D, int EPI, bool COH>
 __device__ __forceinline__ void epilogue_dispatch(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&r)[16],
-                                                  const float* rinv_lds) {
+                                                  const float* rinv_lds, const ResidPre& pre, bool have_pre) {
     if constexpr (EPI >= 0) {
-        gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, r, rinv_lds);
+        gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre);
     } else {
         switch (a.epi) {
             case EPI_QKV: gemm_epilogue<EL, D, EPI_QKV, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
-            case EPI_RESID: gemm_epilogue<EL, D, EPI_RESID, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
+            case EPI_RESID: gemm_epilogue<EL, D, EPI_RESID, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre); break;
             case EPI_SWIGLU: gemm_epilogue<EL, D, EPI_SWIGLU, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
             default: gemm_epilogue<EL, D, EPI_LOGITS, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
         }
@@ -310,6 +310,12 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
                 r[i] = sum;
             }
         }
+        // the residual epilogue's own inputs are requested now, so that they travel while the
+        // partial tiles are exchanged
+        const bool resid = (EPI >= 0) ? (EPI == EPI_RESID) : (a.epi == EPI_RESID);
+        ResidPre pre;
+        const bool mine_out = wave < NT && strip < a.n_strips;
+        if (resid && mine_out) resid_preload(a, Tp, strip, tb_, lane, pre);
         bool finish = (nb == a.NB);   // the whole K range was ours: straight to the epilogue
         if (!finish) {
             // partial tile out with agent-scope atomic stores (write-through: partials and tickets
@@ -350,7 +356,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
                 }
             }
         }
-        if (finish && wave < NT && strip < a.n_strips) epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb_, lane, r, rinv_lds);
+        if (finish && mine_out) epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, resid);
         __syncthreads();   // `red` and ticket_lds are reused
     };
 

@@ -163,7 +163,7 @@ __device__ __forceinline__ void gemm_wide_body(const GemmArgs& a, int wg, float*
                 rr[i] = sum;
             }
             if (whole) {
-                if (strip < a.n_strips) epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb, lane, rr, rinv_lds);
+                if (strip < a.n_strips) epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb, lane, rr, rinv_lds, ResidPre(), false);
             } else {
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
@@ -184,7 +184,7 @@ __device__ __forceinline__ void gemm_wide_body(const GemmArgs& a, int wg, float*
                     for (int tb = 0; tb < TB; ++tb) {
                         float rr[16];
                         wide_sum_partials<TB>(a, ss, wave, tb, lane, c_first, c_last, rr);
-                        epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb, lane, rr, rinv_lds);
+                        epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb, lane, rr, rinv_lds, ResidPre(), false);
                     }
                 }
             }

@@ -138,9 +138,23 @@ struct GemmArgs {
 
 // Epilogue of one 32-row strip x 32-token block, in accumulator layout: lane (tl, g), acc[i] is
 // row 8*(i/4) + 4*g + i%4 of the strip for token tb*32 + tl.
-template <typename EL, int D, int EPI, bool COH = false>
+// Inputs of the residual epilogue that do not depend on the GEMM result: the residual rows and the
+// next norm's gains of this lane's 16 outputs.  A caller that has to wait for something else first
+// (the partial-tile exchange) requests them before that wait and hands them in.
+struct ResidPre { float4 x[4], gain[4]; };
+__device__ __forceinline__ void resid_preload(const GemmArgs& a, int Tp, int strip, int tb, int lane, ResidPre& p) {
+    const int t = tb * 32 + (lane & 31), g = lane >> 5;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+        const int f0 = strip * 32 + 8 * blk + 4 * g;
+        p.x[blk] = ((const float4*)a.x_in)[(size_t)(f0 >> 2) * Tp + t];
+        p.gain[blk] = *(const float4*)(a.gain_next + f0);
+    }
+}
+
+template <typename EL, int D, int EPI, bool COH>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
-                                              const float* rinv_lds) {
+                                              const float* rinv_lds, const ResidPre& pre, bool have_pre) {
     const int tl = lane & 31, g = lane >> 5;
     const int t = tb * 32 + tl;
     if constexpr (EPI == EPI_RESID) {
@@ -148,11 +162,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk) {
             const int f0 = strip * 32 + 8 * blk + 4 * g;
-            float4 xv = ((const float4*)a.x_in)[(size_t)(f0 >> 2) * Tp + t];
+            float4 xv = pre.x[blk], gn = pre.gain[blk];
+            if (!have_pre) { xv = ((const float4*)a.x_in)[(size_t)(f0 >> 2) * Tp + t]; gn = *(const float4*)(a.gain_next + f0); }
             xv.x += acc[4 * blk]; xv.y += acc[4 * blk + 1]; xv.z += acc[4 * blk + 2]; xv.w += acc[4 * blk + 3];
             st_f4<COH>((float4*)a.x + (size_t)(f0 >> 2) * Tp + t, xv);
-            store4_act<EL, COH>(a.xb, Tp, f0, t, xv.x * a.gain_next[f0], xv.y * a.gain_next[f0 + 1],
-                           xv.z * a.gain_next[f0 + 2], xv.w * a.gain_next[f0 + 3]);
+            store4_act<EL, COH>(a.xb, Tp, f0, t, xv.x * gn.x, xv.y * gn.y, xv.z * gn.z, xv.w * gn.w);
             ssq += xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
         }
         ssq += __shfl_xor(ssq, 32);
@@ -229,6 +243,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
             }
         }
     }
+}
+
+template <typename EL, int D, int EPI, bool COH = false>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
+                                              const float* rinv_lds) {
+    ResidPre none;   // never read: have_pre = false
+    gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, acc, rinv_lds, none, false);
 }
 
 template <typename EL, int TB>
