@@ -37,6 +37,20 @@
  * Errors: every int-returning call gives FV_OK (0) or a negative fv_status.  Argument
  * and tree validation happens on the host before anything is launched; a rejected call
  * changes no state and writes no output.
+ *
+ * Environment switches, read once by fv_create (tuning and test aids; every setting computes
+ * the same step and is held to the same parity tests):
+ *   FV_GEMM = paired | direct | wide | shared   GEMM kernel for steps of up to 64 rows.  Default:
+ *       paired (two 32-row strips per wavefront) wherever the K range is long enough, else
+ *       direct (one strip).  wide: four strips per wavefront.  shared: the LDS-shared-activation
+ *       kernel that steps of more than 64 rows always use.
+ *   FV_GEMM_ALIGN = 0 | 1     force the stream-K split (0) or whole row groups per workgroup (1);
+ *       default: whole groups only where that idles at most 10 % of the workgroups.
+ *   FV_GEMM_PAIRED_SET = mask over (QKV, O, gate/up, down, head): matrices that may use the paired form.
+ *   FV_GEMM_WGS = n           workgroups the GEMMs are split over (default 256, one per compute unit).
+ *   FV_PERSISTENT = 1         run all decoder layers of a step of up to 64 rows in one cooperative
+ *       persistent kernel instead of one launch per GEMM.
+ *   FV_PERSIST_TIMING = 1     record time stamps in the persistent kernel (see fv_debug_persist_timing).
  */
 #ifndef FALCON_VERIFY_H
 #define FALCON_VERIFY_H
