@@ -288,6 +288,13 @@ def main():
                      "launches_per_step": n_launch},
         "phase_ms_per_step": {k: v[0] / args.profile_steps for k, v in ph.items()},
     }
+    if ph["attn"][1] > 0:
+        # attention phase against the same roofline: K and V of prefix + tree, once per layer
+        kv_bytes = shape.n_layers * 2 * (L + T) * shape.n_kv_heads * shape.head_dim * shape.elem_bytes()
+        attn_gbs = kv_bytes / (ph["attn"][0] / args.profile_steps * 1e-3) / 1e9
+        out["attention_phase"] = {"achieved": attn_gbs, "unit": "GB/s", "frac": attn_gbs / HBM_PEAK_GBS,
+                                  "bytes_per_step": kv_bytes, "launches_per_step": ph["attn"][1] / args.profile_steps,
+                                  "note": "algorithmic K/V bytes over the per-launch HIP-event time of k_attn (profiling pass)"}
     if args.loop_tokens > 0:
         out["decode_loop"] = decode_loop(fi, gpu, shape, L, root, T, branching, args.loop_tokens, args.loop_p, args.seed)
     traffic = measured_traffic(kname, args, shape)
