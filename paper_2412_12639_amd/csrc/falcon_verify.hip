@@ -464,7 +464,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         const GemmPlan& p = (kind == GEMM_DIRECT) ? ly.gd[which] : (kind == GEMM_PAIRED) ? ly.gp[which] : ly.gm[which];
         GemmArgs ga;
         memset(&ga, 0, sizeof(ga));
-        ga.Wt = (const uint4*)Wt; ga.X = c->at<uint4>(x_off); ga.part = c->at<float>(ly.off_part);
+        ga.Wt = (const uint4*)Wt; ga.X = c->at<uint4>(x_off); ga.part = c->at<float>(ly.off_part); ga.part_bytes = (unsigned)ly.part_bytes;
         ga.tickets = c->at<int>(ly.off_tickets); ga.zeros = c->at<uint4>(ly.off_zeros);
         ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax; ga.aligned = p.aligned;
         ga.tab_u0 = c->at<int>(p.off_tab); ga.tab_g0 = ga.tab_u0 + p.G + 1; ga.tab_cf = ga.tab_g0 + p.G; ga.tab_cl = ga.tab_cf + p.NG;
@@ -772,6 +772,8 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     for (int i = 0; i < GM_COUNT; ++i)   // the direct kernels split their work with 32-bit arithmetic
         for (const GemmPlan* q : {&c->lay.gd[i], &c->lay.gp[i]})
             if ((long long)q->NG * q->NB * (q->G + 1) >= (1LL << 31)) return fail(FV_E_BAD_ARG);
+    // the shared-activation kernel addresses the partial tiles with 32-bit byte offsets
+    if (c->lay.part_bytes >= ((size_t)1 << 31)) return fail(FV_E_BAD_ARG);
     rc = (cfg->dtype == FV_BF16) ? set_gemm_attrs<BF16>(cfg->head_dim) : set_gemm_attrs<F32>(cfg->head_dim);
     if (rc) return fail(rc);
     *out = c;

@@ -27,9 +27,6 @@
 #pragma once
 // (included from fv_kernels.hpp after GemmArgs, gemm_epilogue and zero_acc)
 
-#ifndef FV_TS
-#define FV_TS(k)   // tuning aid: a stand-alone timing harness defines this to record a time stamp
-#endif
 
 // Shared-memory needs, in floats: one accumulator exchange area [4 wavefronts][tiles][16][64],
 // RMSNorm factors [Tp], reduction scratch [1024], ticket.
@@ -38,12 +35,12 @@
 
 template <typename EL, int D, int EPI, bool COH>
 __device__ __forceinline__ void epilogue_dispatch(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&r)[16],
-                                                  const float* rinv_lds, const ResidPre& pre, bool have_pre) {
+                                                  const float* rinv_lds, const EpiPre& pre, bool have_pre) {
     if constexpr (EPI >= 0) {
         gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre);
     } else {
         switch (a.epi) {
-            case EPI_QKV: gemm_epilogue<EL, D, EPI_QKV, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
+            case EPI_QKV: gemm_epilogue<EL, D, EPI_QKV, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre); break;
             case EPI_RESID: gemm_epilogue<EL, D, EPI_RESID, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre); break;
             case EPI_SWIGLU: gemm_epilogue<EL, D, EPI_SWIGLU, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
             default: gemm_epilogue<EL, D, EPI_LOGITS, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
@@ -310,12 +307,15 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
                 r[i] = sum;
             }
         }
-        // the residual epilogue's own inputs are requested now, so that they travel while the
-        // partial tiles are exchanged
+        // what the residual and the rotary epilogues read besides the GEMM result is requested
+        // now, so that it travels while the partial tiles are exchanged
         const bool resid = (EPI >= 0) ? (EPI == EPI_RESID) : (a.epi == EPI_RESID);
-        ResidPre pre;
+        const bool qkv = (EPI >= 0) ? (EPI == EPI_QKV) : (a.epi == EPI_QKV);
+        EpiPre pre;
         const bool mine_out = wave < NT && strip < a.n_strips;
-        if (resid && mine_out) resid_preload(a, Tp, strip, tb_, lane, pre);
+        bool have_pre = false;
+        if (resid && mine_out) { resid_preload(a, Tp, strip, tb_, lane, pre); have_pre = true; }
+        if (qkv && mine_out) have_pre = rope_preload<D>(a, strip, tb_, lane, pre);
         bool finish = (nb == a.NB);   // the whole K range was ours: straight to the epilogue
         if (!finish) {
             // partial tile out with agent-scope atomic stores (write-through: partials and tickets
@@ -356,7 +356,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
                 }
             }
         }
-        if (finish && mine_out) epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, resid);
+        if (finish && mine_out) epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, have_pre);
         __syncthreads();   // `red` and ticket_lds are reused
     };
 

@@ -23,6 +23,10 @@ struct IngestArgs {
     float2* rope_cs;         // [Tp][half_d]  (cos, sin)
 };
 
+#ifndef FV_TS
+#define FV_TS(k)   // tuning aid: a stand-alone timing harness defines this to record a time stamp
+#endif
+
 __global__ __launch_bounds__(256) void k_ingest(IngestArgs a) {
     const int tid = threadIdx.x;
     const int32_t* parent = a.tok_in + a.cap;
@@ -104,7 +108,8 @@ struct GemmArgs {
     const uint4* Wt;     // tiled weights [NG*R strips][NB][FRAGS][64] x 16 B
     const uint4* X;      // vector-major [NB*16][Tp] x 16 B
     const uint4* zeros;  // 32 KiB of zeros (what the direct kernels' padded stages load)
-    float* part;         // [G][segmax][R][TB][64][16] fp32
+    float* part;         // partial tiles, fp32: [G][segmax][tiles of the kernel][1024]
+    unsigned part_bytes; // size of that area (the 128-bit exchange addresses it through a bounds-checked buffer descriptor)
     int* tickets;        // [NG], zero on entry, left zero on exit
     int NG, NB, G, segmax;
     int aligned;         // direct kernels: workgroup ranges end on row-group boundaries (no partial tiles)
@@ -138,11 +143,14 @@ struct GemmArgs {
 
 // Epilogue of one 32-row strip x 32-token block, in accumulator layout: lane (tl, g), acc[i] is
 // row 8*(i/4) + 4*g + i%4 of the strip for token tb*32 + tl.
-// Inputs of the residual epilogue that do not depend on the GEMM result: the residual rows and the
-// next norm's gains of this lane's 16 outputs.  A caller that has to wait for something else first
-// (the partial-tile exchange) requests them before that wait and hands them in.
-struct ResidPre { float4 x[4], gain[4]; };
-__device__ __forceinline__ void resid_preload(const GemmArgs& a, int Tp, int strip, int tb, int lane, ResidPre& p) {
+// Inputs of an epilogue that do not depend on the GEMM result.  A caller that has to wait for
+// something else first (the partial-tile exchange) requests them before that wait and hands them in.
+//   EPI_RESID: x = the residual rows, gain = the next norm's gains of this lane's 16 outputs
+//   EPI_QKV (q and k strips): x[2*pr], x[2*pr+1] = the four (cos, sin) pairs of rotary indices
+//              16*j + 8*pr + 4*g .. +3 at this lane's token
+struct EpiPre { float4 x[4], gain[4]; };
+typedef EpiPre ResidPre;
+__device__ __forceinline__ void resid_preload(const GemmArgs& a, int Tp, int strip, int tb, int lane, EpiPre& p) {
     const int t = tb * 32 + (lane & 31), g = lane >> 5;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
@@ -151,10 +159,23 @@ __device__ __forceinline__ void resid_preload(const GemmArgs& a, int Tp, int str
         p.gain[blk] = *(const float4*)(a.gain_next + f0);
     }
 }
+template <int D>
+__device__ __forceinline__ bool rope_preload(const GemmArgs& a, int strip, int tb, int lane, EpiPre& p) {
+    constexpr int SPH = D / 32;
+    const int t = tb * 32 + (lane & 31), g = lane >> 5, j = strip % SPH;
+    if (strip / SPH >= a.Hq + a.Hkv) return false;   // a v strip: no rotation
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+        const float4* cp = (const float4*)(a.rope_cs + (size_t)t * (D / 2) + 16 * j + 8 * pr + 4 * g);
+        p.x[2 * pr] = cp[0];
+        p.x[2 * pr + 1] = cp[1];
+    }
+    return true;
+}
 
 template <typename EL, int D, int EPI, bool COH>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
-                                              const float* rinv_lds, const ResidPre& pre, bool have_pre) {
+                                              const float* rinv_lds, const EpiPre& pre, bool have_pre) {
     const int tl = lane & 31, g = lane >> 5;
     const int t = tb * 32 + tl;
     if constexpr (EPI == EPI_RESID) {
@@ -202,15 +223,21 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
                 // q or k head: blocks (0,1) and (2,3) are rotary pairs (i, i + D/2)
                 float lo_v[2][4], hi_v[2][4];
 #pragma unroll
-                for (int pr = 0; pr < 2; ++pr)
+                for (int pr = 0; pr < 2; ++pr) {
+                    // (cos, sin) of indices 16*j + 8*pr + 4*g + c in the first half of the head, c = 0..3
+                    float4 c01 = pre.x[2 * pr], c23 = pre.x[2 * pr + 1];
+                    if (!have_pre) {
+                        const float4* cp = (const float4*)(a.rope_cs + (size_t)t * (D / 2) + 16 * j + 8 * pr + 4 * g);
+                        c01 = cp[0]; c23 = cp[1];
+                    }
+                    const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        const int i1 = 16 * j + 8 * pr + 4 * g + c;     // index in the first half of the head
-                        const float2 cs = a.rope_cs[(size_t)t * (D / 2) + i1];
                         const float x1 = acc[8 * pr + c], x2 = acc[8 * pr + 4 + c];
-                        lo_v[pr][c] = x1 * cs.x - x2 * cs.y;
-                        hi_v[pr][c] = x2 * cs.x + x1 * cs.y;
+                        lo_v[pr][c] = x1 * co[c] - x2 * si[c];
+                        hi_v[pr][c] = x2 * co[c] + x1 * si[c];
                     }
+                }
                 if (head < a.Hq) {
 #pragma unroll
                     for (int pr = 0; pr < 2; ++pr) {
@@ -248,7 +275,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 template <typename EL, int D, int EPI, bool COH = false>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
                                               const float* rinv_lds) {
-    ResidPre none;   // never read: have_pre = false
+    EpiPre none;   // never read: have_pre = false
     gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, acc, rinv_lds, none, false);
 }
 
@@ -258,13 +285,21 @@ __device__ __forceinline__ void gemm_compute(const uint4 (&w)[FV_FRAGS], const u
     constexpr int Tp = TB * 32;
     const int t = lane & 31, g = lane >> 5;
     const uint4* xb = xl + g * Tp + t;
+    // The B tiles of fragment f+1 are requested before the MFMAs of fragment f are issued, so an
+    // LDS read has TB MFMAs (32 cycles each) to land in.
+    uint4 b[2][TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) b[0][tb] = xb[tb * 32];
 #pragma unroll
     for (int f = 0; f < FV_FRAGS; ++f) {
-        uint4 b[TB];   // all B tiles of the fragment first, so the LDS reads overlap the MFMAs before them
+        if (f + 1 < FV_FRAGS) {
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) b[tb] = xb[2 * f * Tp + tb * 32];
+            for (int tb = 0; tb < TB; ++tb) b[(f + 1) & 1][tb] = xb[2 * (f + 1) * Tp + tb * 32];
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) acc[tb] = Tr<EL>::mma(w[f], b[tb], acc[tb]);
+        for (int tb = 0; tb < TB; ++tb) acc[tb] = Tr<EL>::mma(w[f], b[f & 1][tb], acc[tb]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -295,78 +330,133 @@ __device__ __forceinline__ void zero_acc(floatx16 (&acc)[TB]) {
 
 // Ends one segment (a run of K batches of one row group): either straight to the epilogue
 // (the segment covered the whole K range) or partials + ticket + last-arriver reduction.
+//
+// Partial tiles cross XCDs, whose L2s are not coherent with each other, so they are written
+// and read with the agent-scope cache policy (write-through stores, loads that do not hit a
+// stale line) and no whole-L2 write-back or invalidate is needed.  They move as 128-bit
+// accesses (layout per tile [4 register quads][64 lanes][4 floats], 1 KiB per wavefront
+// access): a wavefront can have 64 memory operations in flight, and with one-register
+// accesses that cap, not the memory system, set the pace of a reduction over many
+// contributors.  The 128-bit accesses go through a raw buffer descriptor over the partial
+// area, which carries the same policy bit as the agent-scope atomics and bounds-checks
+// every address in hardware.
 template <typename EL, int TB, int D, int EPI>
 __device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB], int gi, int seg_batches, int seg,
                                            const float* rinv_lds, int* ticket_lds) {
     constexpr int R = FV_R;
     constexpr int Tp = TB * 32;
+    constexpr int TG = TB < 4 ? TB : 4;   // tiles handled together: their loads are in flight at the same time
+    // early epilogue inputs; not for the rotary epilogue at 256 tokens, where their registers are spilled
+    constexpr bool PRE = (EPI == EPI_RESID || (EPI == EPI_QKV && TB <= 4));
+    constexpr int SC1 = 16;               // cache-policy operand of the buffer accesses: agent scope
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int strip = gi * R + wave;
+    // what the epilogues of tiles t0 .. t0+TG-1 read besides the GEMM result, requested early
+    auto preload = [&](int t0, EpiPre (&pre)[TG]) -> bool {
+        bool have = false;
+        if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+            for (int tb = 0; tb < TG; ++tb) resid_preload(a, Tp, strip, t0 + tb, lane, pre[tb]);
+            have = true;
+        } else if constexpr (EPI == EPI_QKV) {
+#pragma unroll
+            for (int tb = 0; tb < TG; ++tb) have = rope_preload<D>(a, strip, t0 + tb, lane, pre[tb]);
+        }
+        return have;
+    };
     if (seg_batches == a.NB) {
         // the whole K range of this row group was ours: no partials, no ticket
         if (strip < a.n_strips) {
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                float r[16];
+            for (int t0 = 0; t0 < TB; t0 += TG) {
+                EpiPre pre[TG];
+                const bool have = PRE && preload(t0, pre);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) r[i] = acc[tb][i];
-                gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb, lane, r, rinv_lds);
+                for (int tb = 0; tb < TG; ++tb) {
+                    float r[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) r[i] = acc[t0 + tb][i];
+                    gemm_epilogue<EL, D, EPI, false>(a, Tp, strip, t0 + tb, lane, r, rinv_lds, pre[tb], have);
+                }
             }
         }
         return;
     }
-    // Partials and tickets cross XCDs, whose L2s are not coherent with each other: the
-    // partials are written and read with agent-scope atomic accesses (write-through /
-    // cache-bypassing), so no whole-L2 write-back or invalidate is needed per wavefront.
-    // Layout [tb][16 registers][64 lanes]: every access of a wavefront is one 256-byte line.
-    float* pp = a.part + ((((size_t)blockIdx.x * a.segmax + seg) * R + wave) * TB) * 1024 + lane;
+    const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);   // raw, 32-bit data format
+    auto tile_ofs = [&](int wg, int sg, int tb) -> unsigned {   // byte offset of this lane's first quad of a tile
+        return ((unsigned)(((wg * a.segmax + sg) * R + wave) * TB + tb) * 1024u + (unsigned)lane * 4u) * 4u;
+    };
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
+    for (int tb = 0; tb < TB; ++tb) {
+        const unsigned o = tile_ofs((int)blockIdx.x, seg, tb);
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            __hip_atomic_store(pp + tb * 1024 + i * 64, acc[tb][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int q = 0; q < 4; ++q) {
+            u32x4 v;
+            v.x = __float_as_uint(acc[tb][4 * q]); v.y = __float_as_uint(acc[tb][4 * q + 1]);
+            v.z = __float_as_uint(acc[tb][4 * q + 2]); v.w = __float_as_uint(acc[tb][4 * q + 3]);
+            __builtin_amdgcn_raw_buffer_store_b128(v, prs, o + q * 1024u, 0, SC1);
+        }
+    }
     // contributors of row group gi: workgroups c_first..c_last (each has a non-empty range)
     const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
-    // Release without a whole-L2 write-back: the payload was stored with agent-scope atomic
-    // stores (write-through), so it is enough that every lane's stores have been acknowledged
-    // (vmcnt(0): on this target stores count in vmcnt) before the ticket is drawn.
+    // Release: the payload was stored write-through, so it is enough that every lane's stores
+    // have been acknowledged (vmcnt(0): on this target stores count in vmcnt) before the
+    // ticket is drawn.
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt untouched
+    FV_TS(3)
     __syncthreads();
     if (tid == 0)
         *ticket_lds = __hip_atomic_fetch_add(&a.tickets[gi], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
+    FV_TS(4)
     const bool last = (*ticket_lds == c_last - c_first);
     if (last) {
-        // every other contributor's ticket, hence its acknowledged stores, precede ours; the
-        // partials are read with agent-scope atomic loads, which do not hit stale cache lines
+        // every other contributor's ticket, hence its acknowledged stores, precede ours
         if (tid == 0) __hip_atomic_store(&a.tickets[gi], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
         if (strip < a.n_strips) {
-#pragma unroll 1
-            for (int tb = 0; tb < TB; ++tb) {
-                float r[16];
+            // KC contributors x TG tiles (up to 32 KiB per wavefront) are in flight at a time; the
+            // sum runs in ascending contributor order, so it does not depend on who arrived last
+            constexpr int KC = TG <= 2 ? 4 : (TB <= 4 ? 2 : 1);   // at 256 tokens the activation staging registers leave room for one
 #pragma unroll
-                for (int i = 0; i < 16; ++i) r[i] = 0.f;
-                // four contributions (64 loads) in flight at a time, summed in ascending order
-                for (int c0 = c_first; c0 <= c_last; c0 += 4) {
-                    float v[4][16];
+            for (int t0 = 0; t0 < TB; t0 += TG) {
+                EpiPre pre[TG];
+                const bool have = PRE && preload(t0, pre);
+                float r[TG][16];
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
+                for (int tb = 0; tb < TG; ++tb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) r[tb][i] = 0.f;
+                for (int c0 = c_first; c0 <= c_last; c0 += KC) {
+                    u32x4 v[KC][TG][4];
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) {
                         const int c = (c0 + k <= c_last) ? c0 + k : c_last;
-                        const int cseg = gi - a.tab_g0[c];
-                        const float* cp = a.part + ((((size_t)c * a.segmax + cseg) * R + wave) * TB + tb) * 1024 + lane;
+                        const unsigned o = tile_ofs(c, gi - a.tab_g0[c], t0);
 #pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            v[k][i] = __hip_atomic_load(cp + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        for (int tb = 0; tb < TG; ++tb)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                v[k][tb][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + (tb * 4 + q) * 1024u, 0, SC1);
                     }
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
+                    for (int k = 0; k < KC; ++k) {
                         const float m = (c0 + k <= c_last) ? 1.f : 0.f;
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) r[i] += m * v[k][i];
+                        for (int tb = 0; tb < TG; ++tb)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                r[tb][4 * q] += m * __uint_as_float(v[k][tb][q].x);
+                                r[tb][4 * q + 1] += m * __uint_as_float(v[k][tb][q].y);
+                                r[tb][4 * q + 2] += m * __uint_as_float(v[k][tb][q].z);
+                                r[tb][4 * q + 3] += m * __uint_as_float(v[k][tb][q].w);
+                            }
                     }
                 }
-                gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb, lane, r, rinv_lds);
+                if (t0 == 0) { FV_TS(5) }
+#pragma unroll
+                for (int tb = 0; tb < TG; ++tb) gemm_epilogue<EL, D, EPI, false>(a, Tp, strip, t0 + tb, lane, r[tb], rinv_lds, pre[tb], have);
             }
+            FV_TS(6)
         }
     }
     __syncthreads();   // ticket_lds is reused by the next segment
@@ -385,6 +475,7 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
     __shared__ int ticket_lds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     if ((int)blockIdx.x >= a.G) return;
+    FV_TS(0)
 
     // This workgroup's units [u0, u1) of the (row group, K batch) space are one software-pipelined
     // stream: the weight tiles and the activation chunk of stage k+2 are requested while stage k is
@@ -487,6 +578,7 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
     load_w(w[1]);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    FV_TS(1)
 
     int par = 0;   // LDS buffer that holds the current stage's chunk
     // one pipeline stage with weight register set S; the loads it issues (stage + 2) go to set S2
@@ -516,8 +608,10 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
             FV_STAGE(1, 0)
             FV_STAGE(2, 1)
         }
+        FV_TS(2)
         gemm_flush<EL, TB, D, EPI>(a, acc, gi, nb, sgm, rinv_lds, &ticket_lds);
     }
+    FV_TS(7)
 #undef FV_STAGE
 }
 
