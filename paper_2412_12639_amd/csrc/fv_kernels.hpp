@@ -26,6 +26,11 @@ struct IngestArgs {
 #ifndef FV_TS
 #define FV_TS(k)   // tuning aid: a stand-alone timing harness defines this to record a time stamp
 #endif
+#ifndef FV_PH
+#define FV_PH_DECL   // tuning aid: per-phase cycle sums inside a pipeline stage
+#define FV_PH(k)
+#define FV_PH_END
+#endif
 
 __global__ __launch_bounds__(256) void k_ingest(IngestArgs a) {
     const int tid = threadIdx.x;
@@ -279,14 +284,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
     gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, acc, rinv_lds, none, false);
 }
 
-template <typename EL, int TB>
+// One stage of the shared-activation GEMM for one wavefront: FV_FRAGS weight fragments (registers)
+// times TB activation tiles each (LDS).  The B tiles of fragment f+1 are requested before the
+// MFMAs of fragment f are issued, so an LDS read has TB MFMAs (32 cycles each) to land in;
+// between_frags(f) runs after the MFMAs of fragment f have been issued -- the kernel puts a slice
+// of the next stages' global loads there, so that the texture-address path works through them
+// while the matrix cores are busy instead of after them.
+template <typename EL, int TB, typename Between>
 __device__ __forceinline__ void gemm_compute(const uint4 (&w)[FV_FRAGS], const uint4* __restrict__ xl,
-                                             floatx16 (&acc)[TB], int lane) {
+                                             floatx16 (&acc)[TB], int lane, Between&& between_frags) {
     constexpr int Tp = TB * 32;
     const int t = lane & 31, g = lane >> 5;
     const uint4* xb = xl + g * Tp + t;
-    // The B tiles of fragment f+1 are requested before the MFMAs of fragment f are issued, so an
-    // LDS read has TB MFMAs (32 cycles each) to land in.
     uint4 b[2][TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) b[0][tb] = xb[tb * 32];
@@ -299,6 +308,8 @@ __device__ __forceinline__ void gemm_compute(const uint4 (&w)[FV_FRAGS], const u
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) acc[tb] = Tr<EL>::mma(w[f], b[f & 1][tb], acc[tb]);
+        __builtin_amdgcn_sched_barrier(0);
+        between_frags(f);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -533,7 +544,6 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
 #pragma unroll
         for (int v = 0; v < XV; ++v) dst[v] = *(const u32x4*)(px + v * st);
     };
-
     uint4 w[3][FV_FRAGS];
     u32x4 xr[XV];
     enter(0);
@@ -580,20 +590,33 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
     __syncthreads();
     FV_TS(1)
 
+    FV_PH_DECL
     int par = 0;   // LDS buffer that holds the current stage's chunk
-    // one pipeline stage with weight register set S; the loads it issues (stage + 2) go to set S2
+    // One pipeline stage with weight register set S; the loads it issues (stage + 2) go to set S2.
+    // The chunk of stage + 1 goes from its staging registers to the other LDS buffer first (every
+    // wavefront is past the barrier, so nobody reads that buffer any more); that frees the staging
+    // registers, and the NLD loads of stage + 2 (activation chunk first, then weight tiles) are
+    // issued in slices between the fragments of this stage's multiplication.
+    constexpr int NLD = XV + FV_FRAGS;
 #define FV_STAGE(S, S2)                                                                                 \
     {                                                                                                   \
-        gemm_compute<EL, TB>(w[S], lds + par * CV, acc, lane);                                          \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
         st_lds<XV, 64 * R>(lds + (par ^ 1) * CV + tid, xr);                                             \
         __builtin_amdgcn_sched_barrier(0);                                                              \
+        FV_PH(1)                                                                                        \
         advance();                                                                                      \
-        load_x(xr);                                                                                     \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
-        load_w(w[S2]);                                                                                  \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
+        const bool live_ = rj < rn;                                                                     \
+        const uint4* const px_ = live_ ? xp : zeros;                                                    \
+        const uint4* const pw_ = live_ ? wp : a.Wt;                                                     \
+        const int sx_ = live_ ? 64 * R : 0, sw_ = live_ ? 64 : 0;                                       \
+        gemm_compute<EL, TB>(w[S], lds + par * CV, acc, lane, [&](int f) {                              \
+            _Pragma("unroll") for (int i_ = f * NLD / FV_FRAGS; i_ < (f + 1) * NLD / FV_FRAGS; ++i_) {  \
+                if (i_ < XV) xr[i_] = *(const u32x4*)(px_ + i_ * sx_);                                  \
+                else w[S2][i_ - XV] = pw_[(i_ - XV) * sw_];                                             \
+            }                                                                                           \
+        });                                                                                             \
+        FV_PH(0)                                                                                        \
         __syncthreads();                                                                                \
+        FV_PH(3)                                                                                        \
         par ^= 1;                                                                                       \
     }
 
@@ -612,6 +635,7 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
         gemm_flush<EL, TB, D, EPI>(a, acc, gi, nb, sgm, rinv_lds, &ticket_lds);
     }
     FV_TS(7)
+    FV_PH_END
 #undef FV_STAGE
 }
 
