@@ -104,6 +104,15 @@ template <> __device__ __forceinline__ void st_elem<BF16, true>(void* p, size_t 
 }
 template <> __device__ __forceinline__ void st_elem<F32, true>(void* p, size_t i, float v) { st_f32<true>((float*)p + i, v); }
 
+// four consecutive cache elements starting at element index i (i % 4 == 0)
+template <typename EL, bool COH> __device__ __forceinline__ void st_cache4(void* p, size_t i, const float (&v)[4]) {
+    if constexpr (Tr<EL>::E == 8) {
+        st_u64<COH>((char*)p + i * 2, (uint64_t)pack_bf16x2(v[0], v[1]) | ((uint64_t)pack_bf16x2(v[2], v[3]) << 32));
+    } else {
+        st_f4<COH>((float4*)((float*)p + i), make_float4(v[0], v[1], v[2], v[3]));
+    }
+}
+
 // Store four consecutive features f0..f0+3 (f0 % 4 == 0) of token t into a vector-major
 // activation buffer.
 template <typename EL, bool COH = false>

@@ -254,14 +254,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
                     const int kh = head - a.Hq;
                     char* slab = (char*)a.kcache + (size_t)kh * a.S_pad * D * Tr<EL>::ESZ;
                     const int pos = a.L + t;   // cache SLOT of tree node t (its rotary position is L + depth)
+                    // four consecutive features of one position are contiguous in the slab (they lie in
+                    // one 2E-feature fragment row): one 8- or 16-byte store each
 #pragma unroll
-                    for (int pr = 0; pr < 2; ++pr)
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            const int f1 = 16 * j + 8 * pr + 4 * g + c;
-                            st_elem<EL, COH>(slab, kcache_index<EL, D>(pos, f1), lo_v[pr][c]);
-                            st_elem<EL, COH>(slab, kcache_index<EL, D>(pos, f1 + D / 2), hi_v[pr][c]);
-                        }
+                    for (int pr = 0; pr < 2; ++pr) {
+                        const int f1 = 16 * j + 8 * pr + 4 * g;
+                        st_cache4<EL, COH>(slab, kcache_index<EL, D>(pos, f1), lo_v[pr]);
+                        st_cache4<EL, COH>(slab, kcache_index<EL, D>(pos, f1 + D / 2), hi_v[pr]);
+                    }
                 }
             } else if (t < a.T) {
                 const int kh = head - a.Hq - a.Hkv;
