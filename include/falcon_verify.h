@@ -48,6 +48,9 @@
  *       default: whole groups only where that idles at most 10 % of the workgroups.
  *   FV_GEMM_PAIRED_SET = mask over (QKV, O, gate/up, down, head): matrices that may use the paired form.
  *   FV_GEMM_WGS = n           workgroups the GEMMs are split over (default 256, one per compute unit).
+ *   FV_GEMM_FIX = 0           steps of more than 64 rows: let the last workgroup to arrive reduce a row group's
+ *       partial tiles inside the GEMM launch (default: a second launch reduces them, one wavefront per tile,
+ *       for the QKV, O and down projections).
  *   FV_PERSISTENT = 1         run all decoder layers of a step of up to 64 rows in one cooperative
  *       persistent kernel instead of one launch per GEMM.
  *   FV_PERSIST_TIMING = 1     record time stamps in the persistent kernel (see fv_debug_persist_timing).

@@ -31,7 +31,8 @@ struct GemmPlan {
     int G = 0, segmax = 0;
     int aligned = 0;   // workgroup ranges end on row-group boundaries
     size_t tiled_bytes = 0;
-    size_t off_tab = 0;   // device tables: u0[G+1], g0[G], cf[NG], cl[NG]
+    size_t off_tab = 0;   // device tables: u0[G+1], g0[G], cf[NG], cl[NG], fix[NG] (row groups with several contributors)
+    int n_fix = 0;        // entries of fix[]
 };
 
 enum { GM_QKV = 0, GM_O = 1, GM_GU = 2, GM_DN = 3, GM_LM = 4, GM_COUNT = 5 };
@@ -96,13 +97,14 @@ void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R, 
 
 // The stream-K split of one GEMM: workgroup w owns units [u0[w], u0[w+1]) of the (row group,
 // K batch) space; g0[w] is its first row group; row group gi is shared by workgroups cf[gi]..cl[gi].
-void build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
+int build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
     const long long U = (long long)p.NG * p.NB;
-    tab.assign((size_t)2 * p.G + 1 + 2 * p.NG, 0);
+    tab.assign((size_t)2 * p.G + 1 + 3 * p.NG, 0);
     int* u0 = tab.data();
     int* g0 = u0 + p.G + 1;
     int* cf = g0 + p.G;
     int* cl = cf + p.NG;
+    int* fix = cl + p.NG;
     for (int w = 0; w <= p.G; ++w) u0[w] = p.aligned ? (int)((long long)p.NG * w / p.G) * p.NB : (int)(U * w / p.G);
     for (int w = 0; w < p.G; ++w) g0[w] = u0[w] / p.NB;
     for (int gi = 0; gi < p.NG; ++gi) { cf[gi] = p.G; cl[gi] = -1; }
@@ -111,6 +113,9 @@ void build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
             if (w < cf[gi]) cf[gi] = w;
             if (w > cl[gi]) cl[gi] = w;
         }
+    int n_fix = 0;
+    for (int gi = 0; gi < p.NG; ++gi) if (cl[gi] > cf[gi]) fix[n_fix++] = gi;
+    return n_fix;
 }
 
 void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
@@ -180,9 +185,9 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     for (int i = 0; i < GM_COUNT; ++i) if (L.gm[i].n_strips_pad > ngmax) ngmax = L.gm[i].n_strips_pad;
     L.off_tickets = take((size_t)ngmax * 4);
     for (int i = 0; i < GM_COUNT; ++i) {
-        L.gm[i].off_tab = take((size_t)(2 * L.gm[i].G + 1 + 2 * L.gm[i].NG) * 4);
-        L.gd[i].off_tab = take((size_t)(2 * L.gd[i].G + 1 + 2 * L.gd[i].NG) * 4);
-        L.gp[i].off_tab = take((size_t)(2 * L.gp[i].G + 1 + 2 * L.gp[i].NG) * 4);
+        L.gm[i].off_tab = take((size_t)(2 * L.gm[i].G + 1 + 3 * L.gm[i].NG) * 4);
+        L.gd[i].off_tab = take((size_t)(2 * L.gd[i].G + 1 + 3 * L.gd[i].NG) * 4);
+        L.gp[i].off_tab = take((size_t)(2 * L.gp[i].G + 1 + 3 * L.gp[i].NG) * 4);
     }
     L.off_zeros = take(32768);   // never written after the arena is cleared
     L.off_stepin = take(3 * FV_MAX_TREE * 4);
@@ -259,6 +264,7 @@ struct fv_ctx {
     bool profiling = false;
     int kind[GM_COUNT];       // GemmKind per matrix, used up to 64 tokens
     bool persistent_ok = false;  // persistent step kernel asked for (FV_PERSISTENT=1) and cooperative launch available
+    int gemm_fix = 1;            // 128 / 256 tokens: separate reduction launch for QKV, O and down (FV_GEMM_FIX=0: off, 2: every GEMM)
     bool last_persistent = false;
     unsigned bar_gen = 0;
     int* h_err = nullptr;        // pinned copy of the persistent kernel's error flag   // FV_GEMM=shared: use the LDS-shared kernel for every token count (tuning)
@@ -294,10 +300,20 @@ struct PhaseTimer {   // brackets launches with events when profiling is on
 };
 
 template <typename EL, int TB, int D, int EPI>
-int launch_gemm_t(fv_ctx* c, const GemmArgs& ga) {
+int launch_gemm_t(fv_ctx* c, const GemmArgs& ga0) {
     const size_t lds = (size_t)2 * TB * 32 * 256;
+    GemmArgs ga = ga0;
+    // At 128 / 256 tokens the projections with heavy fix-ups (QKV: rotary epilogue on 4 / 8 tiles per
+    // wavefront; O and down: 8 contributors per row group) leave the reduction to k_gemm_fix.
+    ga.defer = (TB >= 4 && ((c->gemm_fix == 1 && (EPI == EPI_QKV || EPI == EPI_RESID)) || c->gemm_fix == 2) && ga.n_fix > 0) ? 1 : 0;
     hipLaunchKernelGGL((k_gemm<EL, TB, D, EPI>), dim3(ga.G), dim3(64 * FV_R), lds, c->stream, ga);
-    return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
+    if (hipGetLastError() != hipSuccess) return FV_E_HIP;
+    if (ga.defer) {
+        const int tiles = ga.n_fix * FV_R * TB;
+        hipLaunchKernelGGL((k_gemm_fix<EL, TB, D, EPI>), dim3((tiles + 3) / 4), dim3(256), 0, c->stream, ga);
+        if (hipGetLastError() != hipSuccess) return FV_E_HIP;
+    }
+    return FV_OK;
 }
 
 template <typename EL, int TB, int D, int EPI>
@@ -468,6 +484,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         ga.tickets = c->at<int>(ly.off_tickets); ga.zeros = c->at<uint4>(ly.off_zeros);
         ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax; ga.aligned = p.aligned;
         ga.tab_u0 = c->at<int>(p.off_tab); ga.tab_g0 = ga.tab_u0 + p.G + 1; ga.tab_cf = ga.tab_g0 + p.G; ga.tab_cl = ga.tab_cf + p.NG;
+        ga.fix_groups = ga.tab_cl + p.NG; ga.n_fix = p.n_fix; ga.rinv_out = c->at<float>(ly.off_rinv);
         ga.T = T; ga.n_strips = p.n_strips;
         ga.ssq_in = c->at<float>(ly.off_ssq); ga.n_ssq = h / 32; ga.inv_h = 1.f / (float)h; ga.eps = cf.rms_eps;
         return ga;
@@ -747,6 +764,7 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     // the persistent kernel (which wins nothing from its cheaper phase boundaries once 32 layers of
     // rotating activation slots stop fitting the L2s).  FV_PERSISTENT=1 selects the persistent kernel.
     { const char* e = getenv("FV_PERSISTENT"); c->persistent_ok = e && !strcmp(e, "1"); }
+    { const char* e = getenv("FV_GEMM_FIX"); c->gemm_fix = e ? atoi(e) : 1; }
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipHostMalloc((void**)&c->h_res, sizeof(FvResult), hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
@@ -764,9 +782,9 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     if (hipMemsetAsync(c->arena + z0, 0, c->lay.total - z0, c->stream) != hipSuccess) return fail(FV_E_HIP);
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(FV_E_HIP);
     for (int k = 0; k < 3 * GM_COUNT; ++k) {
-        const GemmPlan& p = (k < GM_COUNT) ? c->lay.gm[k] : (k < 2 * GM_COUNT) ? c->lay.gd[k - GM_COUNT] : c->lay.gp[k - 2 * GM_COUNT];
+        GemmPlan& p = (k < GM_COUNT) ? c->lay.gm[k] : (k < 2 * GM_COUNT) ? c->lay.gd[k - GM_COUNT] : c->lay.gp[k - 2 * GM_COUNT];
         std::vector<int> tab;
-        build_split_tables(p, tab);
+        p.n_fix = build_split_tables(p, tab);
         if (hipMemcpy(c->arena + p.off_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) return fail(FV_E_HIP);
     }
     for (int i = 0; i < GM_COUNT; ++i)   // the direct kernels split their work with 32-bit arithmetic

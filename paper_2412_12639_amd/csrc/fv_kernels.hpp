@@ -121,6 +121,12 @@ struct GemmArgs {
     // stream-K split, precomputed on the host: range start of every workgroup (G+1 entries), its
     // first row group, and the first / last contributing workgroup of every row group
     const int* tab_u0; const int* tab_g0; const int* tab_cf; const int* tab_cl;
+    // Deferred reduction (shared-activation kernel, 128 / 256 tokens): a segment that does not cover
+    // the whole K range only stores its partial tiles, and k_gemm_fix, launched right behind, reduces
+    // the n_fix row groups that have several contributors with one wavefront per tile.
+    int defer, n_fix;
+    const int* fix_groups;   // [n_fix] row groups with more than one contributor
+    float* rinv_out;         // [Tp] RMSNorm factors handed from k_gemm to k_gemm_fix
     int T, n_strips;     // real tokens; strips that carry real rows
     int epi;             // epilogue, for bodies that choose it at run time
     // RMSNorm statistics of the input (QKV, SWIGLU, LOGITS): rinv[t] = rsqrt(sum_s ssq_in[s][t] / h + eps)
@@ -408,6 +414,7 @@ __device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB
             __builtin_amdgcn_raw_buffer_store_b128(v, prs, o + q * 1024u, 0, SC1);
         }
     }
+    if (a.defer) return;   // reduced by k_gemm_fix after this launch (the launch boundary orders the two)
     // contributors of row group gi: workgroups c_first..c_last (each has a non-empty range)
     const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
     // Release: the payload was stored write-through, so it is enough that every lane's stores
@@ -574,7 +581,9 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
             float tot = 0.f;
 #pragma unroll
             for (int p = 0; p < SL; ++p) tot += red_lds[p * Tp + tid];
-            rinv_lds[tid] = rsqrtf(tot * a.inv_h + a.eps);
+            const float rv = rsqrtf(tot * a.inv_h + a.eps);
+            rinv_lds[tid] = rv;
+            if (a.defer && blockIdx.x == 0) a.rinv_out[tid] = rv;
         }
     }
     // X(0) -> LDS[0]; then X(1) and W(1) are issued in the same order as inside the loop
@@ -637,6 +646,61 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
     FV_TS(7)
     FV_PH_END
 #undef FV_STAGE
+}
+
+// Second half of a deferred reduction: one wavefront per (row group with several contributors,
+// strip, token block) tile sums the contributors' partial tiles in ascending workgroup order and
+// runs the epilogue.  Spreading the tiles over the whole chip instead of leaving each row group
+// to its last arriver matters at 128 / 256 tokens, where a row group's partials are 0.5-1 MiB and
+// one CU pulls them in at ~60 GB/s.
+template <typename EL, int TB, int D, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_fix(GemmArgs a) {
+    constexpr int R = FV_R;
+    constexpr int Tp = TB * 32;
+    constexpr int SC1 = 16;
+    __shared__ float rinv_lds[Tp];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if constexpr (EPI != EPI_RESID) {
+        if (tid < Tp) rinv_lds[tid] = a.rinv_out[tid];
+        __syncthreads();
+    }
+    const int tile = blockIdx.x * 4 + wave;
+    if (tile >= a.n_fix * R * TB) return;
+    const int gi = a.fix_groups[tile / (R * TB)];
+    const int r = (tile / TB) % R, tb = tile % TB;
+    const int strip = gi * R + r;
+    if (strip >= a.n_strips) return;
+    EpiPre pre;
+    bool have = false;
+    if constexpr (EPI == EPI_RESID) { resid_preload(a, Tp, strip, tb, lane, pre); have = true; }
+    if constexpr (EPI == EPI_QKV) have = rope_preload<D>(a, strip, tb, lane, pre);
+    const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
+    const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
+    float acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int c0 = c_first; c0 <= c_last; c0 += 4) {   // four contributors in flight, summed in ascending order
+        u32x4 v[4][4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int c = (c0 + k <= c_last) ? c0 + k : c_last;
+            const unsigned o = ((unsigned)(((c * a.segmax + (gi - a.tab_g0[c])) * R + r) * TB + tb) * 1024u + (unsigned)lane * 4u) * 4u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[k][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + q * 1024u, 0, SC1);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float m = (c0 + k <= c_last) ? 1.f : 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                acc[4 * q] += m * __uint_as_float(v[k][q].x);
+                acc[4 * q + 1] += m * __uint_as_float(v[k][q].y);
+                acc[4 * q + 2] += m * __uint_as_float(v[k][q].z);
+                acc[4 * q + 3] += m * __uint_as_float(v[k][q].w);
+            }
+        }
+    }
+    gemm_epilogue<EL, D, EPI, false>(a, Tp, strip, tb, lane, acc, rinv_lds, pre, have);
 }
 
 #include "fv_gemm_direct.hpp"
