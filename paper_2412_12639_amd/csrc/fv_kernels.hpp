@@ -769,16 +769,17 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
     const int nkb = (n_keys + 31) >> 5;
     const int kb_lo = nkb * part / a.ks, kb_hi = nkb * (part + 1) / a.ks;   // this workgroup's key blocks
     const int lidx = tl * 2 + g;   // position of this lane's 16 bytes inside a 1 KiB tile
-    for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
-        // all K and V tiles of the block are requested before the first is used: one memory round
-        // trip per block instead of two (a workgroup handles only one or two blocks per wavefront)
+    // all K and V tiles of a block are requested before the first is used: one memory round trip
+    // per block instead of two
+    auto load_block = [&](uint4 (&kt)[NF], uint4 (&vt)[DB * NQ], int kb) {
         const uint4* kp = kslab + (size_t)kb * NF * 64 + lidx;
         const uint4* vp = vslab + (size_t)kb * DB * NQ * 64 + lidx;
-        uint4 kt[NF], vt[DB * NQ];
 #pragma unroll
         for (int fr = 0; fr < NF; ++fr) kt[fr] = kp[fr * 64];
 #pragma unroll
         for (int j = 0; j < DB * NQ; ++j) vt[j] = vp[j * 64];
+    };
+    auto use_block = [&](const uint4 (&kt)[NF], const uint4 (&vt)[DB * NQ], int kb) {
         floatx16 s;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[i] = 0.f;
@@ -820,6 +821,11 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
 #pragma unroll
             for (int q = 0; q < NQ; ++q) o[db] = Tr<EL>::mma(vt[db * NQ + q], pb[q], o[db]);
         }
+    };
+    for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
+        uint4 kt[NF], vt[DB * NQ];
+        load_block(kt, vt, kb);
+        use_block(kt, vt, kb);
     }
     l_run += __shfl_xor(l_run, 32);
 
@@ -930,7 +936,20 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
 template <typename EL, int D>
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) float smem[FV_ATTN_SMEM_FLOATS(D)];
-    attn_body<EL, D, false>(a, blockIdx.x / a.ks, blockIdx.x % a.ks, smem);
+    // Workgroups go to the 8 XCDs round-robin (workgroup b runs on XCD b % 8) and every XCD has its
+    // own L2, so all node blocks and key parts of a query head -- and the query heads that share a
+    // KV head -- are given to workgroups of one XCD: a head's K/V then comes from HBM once and is
+    // re-read from that L2, instead of once per XCD that touches it.  (Only locality depends on the
+    // dispatch order; any other order computes the same thing.)
+    int item = blockIdx.x / a.ks, part = blockIdx.x % a.ks;
+    if ((a.Hq & 7) == 0) {
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int TB = a.Tp >> 5, per_head = TB * a.ks;
+        const int head = x * (a.Hq >> 3) + j / per_head, w = j % per_head;
+        item = head * TB + w / a.ks;
+        part = w % a.ks;
+    }
+    attn_body<EL, D, false>(a, item, part, smem);
 }
 
 #include "fv_step_persistent.hpp"

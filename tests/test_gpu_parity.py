@@ -120,6 +120,24 @@ def test_verify_planted_tree(fvmod, name, n, br, plant, L):
 
 
 @pytest.mark.parametrize("name", ["small-gqa-f32", "small-gqa"])
+def test_long_prefix_large_tree(fvmod, name):
+    """A prefix long enough that every attention wavefront walks several key blocks, under a 200-node tree."""
+    L, n = 1700, 200
+    s, w = SHAPES[name], weights_of(name)
+    tol = H.tol_for(s)
+    say("long prefix", name, L, n)
+    case = H.planted_case(s, w, L, n, fi.random_branching(n, n), 3, seed=L + n)
+    g = make_gpu(fvmod, s, w, max_seq=L + n + 8, max_tree=256)
+    assert g.prefill(case["prefix"]) == case["root"]
+    got = g.verify_tree(case["tokens"], case["parent"], case["depth"])
+    e = H.check_step(g, case, got, tol)
+    say("logits err", e, "accepted", got[0])
+    assert got[0] == 3
+    H.check_cache(g, case["oracle"], s, L + 3 + 1, tol)
+    g.close()
+
+
+@pytest.mark.parametrize("name", ["small-gqa-f32", "small-gqa"])
 @pytest.mark.parametrize("n", [1, 2, 16, 33, 64, 100, 128, 200, 256])
 def test_tree_sizes_and_ragged_rows(fvmod, name, n):
     """All token-block instantiations (32/64/128/256 padded rows) with ragged fills."""
