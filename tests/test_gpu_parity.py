@@ -334,6 +334,41 @@ def test_alternative_gemm_kernels_match_the_oracle(fvmod, name, kind, monkeypatc
         g.close()
 
 
+@pytest.mark.parametrize("name", ["small-gqa-f32", "small-gqa"])
+@pytest.mark.parametrize("mode", ["0", "1", "2"])
+def test_partial_tile_reduction_modes_above_64_rows(fvmod, name, mode, monkeypatch):
+    """Steps of 128 / 256 rows: the partial tiles of a row group are reduced by the last workgroup to
+    arrive inside the GEMM launch (FV_GEMM_FIX=0), by a second launch with one wavefront per tile for
+    QKV, O and down (1, the default), or by that launch for every GEMM (2).  Same bar for each.  All
+    three sum in ascending workgroup order, but the epilogue is compiled into two kernels whose
+    multiply-adds may be contracted differently, so across modes the fp32 logits are only required to
+    agree to rounding (1e-5 of the row maximum), not bit for bit."""
+    s, w = SHAPES[name], weights_of(name)
+    tol = H.tol_for(s)
+    monkeypatch.setenv("FV_GEMM_FIX", mode)
+    for n_nodes in (100, 256):
+        say("reduction mode", mode, name, n_nodes)
+        case = H.planted_case(s, w, 45, n_nodes, fi.random_branching(n_nodes, n_nodes), 3, seed=n_nodes)
+        g = make_gpu(fvmod, s, w, max_seq=45 + n_nodes + 8, max_tree=256)
+        assert g.prefill(case["prefix"]) == case["root"]
+        got = g.verify_tree(case["tokens"], case["parent"], case["depth"])
+        e = H.check_step(g, case, got, tol)
+        say("FV_GEMM_FIX=" + mode, n_nodes, "nodes: err", e)
+        logits = g.logits(n_nodes).copy()
+        key = (name, n_nodes)
+        if key in _REDUCTION_LOGITS:
+            if s.dtype == "f32":
+                d = H.row_rel_err(logits.astype(np.float64), _REDUCTION_LOGITS[key].astype(np.float64))
+                say("distance to the first mode's logits", d.max())
+                assert d.max() <= 1e-5
+        else:
+            _REDUCTION_LOGITS[key] = logits
+        g.close()
+
+
+_REDUCTION_LOGITS = {}
+
+
 def _full_size_case(s, w, L, n_nodes, branching, plant, seed, deep=False):
     """One seeded instance at benchmark size, no search for comfortable margins (the oracle pass is
     too slow to repeat): prefix, tree with the oracle's greedy tokens planted, oracle results.
