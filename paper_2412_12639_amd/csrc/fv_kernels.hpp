@@ -786,45 +786,68 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
 #pragma unroll
         for (int fr = 0; fr < NF; ++fr) s = Tr<EL>::mma(kt[fr], qf[fr], s);
 
+        // Visibility of the block's 32 keys for this lane's node as one 32-bit word (bit j: key
+        // kb*32 + j): prefix keys are visible to every node, a tree key n only if bit n of the node's
+        // ancestor mask is set (the mask has no bits at or above T).  The block's offset into the
+        // tree, n0, is the same for the whole wavefront, so the window is cut out of the 256-bit
+        // mask with uniform shifts and no per-element branch.
+        uint32_t vbits = 0xffffffffu;
+        const int n0 = kb * 32 - a.L;   // tree index of the block's first key
+        if (n0 > -32) {
+            uint32_t win;
+            if (n0 < 0) {
+                win = ((1u << (-n0)) - 1u) | ((uint32_t)mk[0] << (-n0));
+            } else {
+                const int w = n0 >> 6, sh = n0 & 63;
+                const uint64_t lo = (w == 0) ? mk[0] : (w == 1) ? mk[1] : (w == 2) ? mk[2] : (w == 3) ? mk[3] : 0ull;
+                const uint64_t hi = (w == 0) ? mk[1] : (w == 1) ? mk[2] : (w == 2) ? mk[3] : 0ull;
+                win = (uint32_t)(sh ? ((lo >> sh) | (hi << (64 - sh))) : lo);
+            }
+            vbits = win >> (4 * g);
+        }
         float p[16];
         float mx = -1e30f;
-        const bool all_prefix = (kb * 32 + 32 <= a.L);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int key = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-            bool vis = true;
-            if (!all_prefix) {
-                const int n = key - a.L;   // tree index of this key if >= 0
-                vis = (n < 0) || (n < a.T && ((mk[(n >> 6) & 3] >> (n & 63)) & 1ull));
-            }
+            const bool vis = (vbits >> (8 * (i >> 2) + (i & 3))) & 1u;   // key 8*(i/4) + 4*g + i%4 of the block
             p[i] = vis ? s[i] * a.scale : -1e30f;
             mx = fmaxf(mx, p[i]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __expf(m_run - m_new);
+        // Lazy rescale: the running reference m_run only has to be near the running maximum, not equal
+        // to it -- exp(score - m_run) stays below e^8 as long as no row's maximum has grown by more than
+        // 8 since the reference was set, which fp32 sums and bf16 probabilities hold without loss.  The
+        // accumulators (64 registers, a read-multiply-write each) are rescaled only when some row of the
+        // wavefront crosses that bound; after the first blocks of a long key range that is rare.
+        const float m_cand = fmaxf(m_run, mx);
+        if (__any(m_cand - m_run > 8.f)) {
+            const float alpha = __expf(m_run - m_cand);
+            l_run *= alpha;
+            m_run = m_cand;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        }
         float psum = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            p[i] = (p[i] > -1e29f) ? __expf(p[i] - m_new) : 0.f;
+            p[i] = (p[i] > -1e29f) ? __expf(p[i] - m_run) : 0.f;
             psum += p[i];
         }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+        l_run += psum;
         uint4 pb[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q) pb[q] = Tr<EL>::pack(p + q * E);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int q = 0; q < NQ; ++q) o[db] = Tr<EL>::mma(vt[db * NQ + q], pb[q], o[db]);
-        }
     };
     for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
         uint4 kt[NF], vt[DB * NQ];
         load_block(kt, vt, kb);
+        __builtin_amdgcn_sched_barrier(0);   // the 16 requests stay together, ahead of everything that uses them
         use_block(kt, vt, kb);
     }
     l_run += __shfl_xor(l_run, 32);
