@@ -326,6 +326,10 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
                 for (int i = 0; i < 16; ++i) __hip_atomic_store(pp + i * 64, r[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
+            // Segment index of this row group inside a contributor's partial area: the ranges are
+            // contiguous, so every contributor but the first starts inside the group (index 0); the
+            // first one's index is fetched now, not between the ticket and the partial loads.
+            const int seg_first = gi - a.tab_g0[c_first];
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): stores count in vmcnt on this target
             __syncthreads();
             if (tid == 0) *ticket_lds = __hip_atomic_fetch_add(&a.tickets[gi], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -341,7 +345,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
 #pragma unroll
                         for (int k = 0; k < 2; ++k) {
                             const int c = (c0 + k <= c_last) ? c0 + k : c_last;
-                            const int cseg = gi - a.tab_g0[c];
+                            const int cseg = (c == c_first) ? seg_first : 0;
                             const float* cp = a.part + (((size_t)c * a.segmax + cseg) * NT + wave) * 1024 + lane;
 #pragma unroll
                             for (int i = 0; i < 16; ++i) v[k][i] = __hip_atomic_load(cp + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

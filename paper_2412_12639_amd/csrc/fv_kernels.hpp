@@ -415,8 +415,11 @@ __device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB
         }
     }
     if (a.defer) return;   // reduced by k_gemm_fix after this launch (the launch boundary orders the two)
-    // contributors of row group gi: workgroups c_first..c_last (each has a non-empty range)
+    // contributors of row group gi: workgroups c_first..c_last (each has a non-empty range); the
+    // ranges are contiguous, so every contributor but the first starts inside the group (its
+    // segment index for it is 0)
     const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
+    const int seg_first = gi - a.tab_g0[c_first];
     // Release: the payload was stored write-through, so it is enough that every lane's stores
     // have been acknowledged (vmcnt(0): on this target stores count in vmcnt) before the
     // ticket is drawn.
@@ -449,7 +452,7 @@ __device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
                         const int c = (c0 + k <= c_last) ? c0 + k : c_last;
-                        const unsigned o = tile_ofs(c, gi - a.tab_g0[c], t0);
+                        const unsigned o = tile_ofs(c, (c == c_first) ? seg_first : 0, t0);
 #pragma unroll
                         for (int tb = 0; tb < TG; ++tb)
 #pragma unroll
@@ -675,6 +678,7 @@ __global__ __launch_bounds__(256) void k_gemm_fix(GemmArgs a) {
     if constexpr (EPI == EPI_RESID) { resid_preload(a, Tp, strip, tb, lane, pre); have = true; }
     if constexpr (EPI == EPI_QKV) have = rope_preload<D>(a, strip, tb, lane, pre);
     const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
+    const int seg_first = gi - a.tab_g0[c_first];   // every later contributor starts inside the group: index 0
     const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
     float acc[16];
 #pragma unroll
@@ -684,7 +688,7 @@ __global__ __launch_bounds__(256) void k_gemm_fix(GemmArgs a) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int c = (c0 + k <= c_last) ? c0 + k : c_last;
-            const unsigned o = ((unsigned)(((c * a.segmax + (gi - a.tab_g0[c])) * R + r) * TB + tb) * 1024u + (unsigned)lane * 4u) * 4u;
+            const unsigned o = ((unsigned)(((c * a.segmax + ((c == c_first) ? seg_first : 0)) * R + r) * TB + tb) * 1024u + (unsigned)lane * 4u) * 4u;
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[k][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + q * 1024u, 0, SC1);
         }
