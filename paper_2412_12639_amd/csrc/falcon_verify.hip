@@ -31,7 +31,8 @@ struct GemmPlan {
     int G = 0, segmax = 0;
     int aligned = 0;   // workgroup ranges end on row-group boundaries
     size_t tiled_bytes = 0;
-    size_t off_tab = 0;   // device tables: u0[G+1], g0[G], cf[NG], cl[NG], fix[NG] (row groups with several contributors)
+    size_t off_tab = 0;   // device tables: u0[G+1], g0[G], cf[NG], cl[NG], fix[NG][4] (row groups with several contributors:
+                          // group, first and last contributor, the first one's segment index)
     int n_fix = 0;        // entries of fix[]
 };
 
@@ -99,12 +100,13 @@ void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R, 
 // K batch) space; g0[w] is its first row group; row group gi is shared by workgroups cf[gi]..cl[gi].
 int build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
     const long long U = (long long)p.NG * p.NB;
-    tab.assign((size_t)2 * p.G + 1 + 3 * p.NG, 0);
+    const size_t fix_at = ((size_t)2 * p.G + 1 + 2 * p.NG + 3) & ~(size_t)3;   // 16-byte aligned records
+    tab.assign(fix_at + 4 * (size_t)p.NG, 0);
     int* u0 = tab.data();
     int* g0 = u0 + p.G + 1;
     int* cf = g0 + p.G;
     int* cl = cf + p.NG;
-    int* fix = cl + p.NG;
+    int* fix = u0 + fix_at;
     for (int w = 0; w <= p.G; ++w) u0[w] = p.aligned ? (int)((long long)p.NG * w / p.G) * p.NB : (int)(U * w / p.G);
     for (int w = 0; w < p.G; ++w) g0[w] = u0[w] / p.NB;
     for (int gi = 0; gi < p.NG; ++gi) { cf[gi] = p.G; cl[gi] = -1; }
@@ -114,7 +116,11 @@ int build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
             if (w > cl[gi]) cl[gi] = w;
         }
     int n_fix = 0;
-    for (int gi = 0; gi < p.NG; ++gi) if (cl[gi] > cf[gi]) fix[n_fix++] = gi;
+    for (int gi = 0; gi < p.NG; ++gi)
+        if (cl[gi] > cf[gi]) {
+            int* rec = fix + 4 * n_fix++;
+            rec[0] = gi; rec[1] = cf[gi]; rec[2] = cl[gi]; rec[3] = gi - g0[cf[gi]];
+        }
     return n_fix;
 }
 
@@ -185,9 +191,9 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     for (int i = 0; i < GM_COUNT; ++i) if (L.gm[i].n_strips_pad > ngmax) ngmax = L.gm[i].n_strips_pad;
     L.off_tickets = take((size_t)ngmax * 4);
     for (int i = 0; i < GM_COUNT; ++i) {
-        L.gm[i].off_tab = take((size_t)(2 * L.gm[i].G + 1 + 3 * L.gm[i].NG) * 4);
-        L.gd[i].off_tab = take((size_t)(2 * L.gd[i].G + 1 + 3 * L.gd[i].NG) * 4);
-        L.gp[i].off_tab = take((size_t)(2 * L.gp[i].G + 1 + 3 * L.gp[i].NG) * 4);
+        L.gm[i].off_tab = take((size_t)(2 * L.gm[i].G + 1 + 6 * L.gm[i].NG) * 4 + 16);
+        L.gd[i].off_tab = take((size_t)(2 * L.gd[i].G + 1 + 6 * L.gd[i].NG) * 4 + 16);
+        L.gp[i].off_tab = take((size_t)(2 * L.gp[i].G + 1 + 6 * L.gp[i].NG) * 4 + 16);
     }
     L.off_zeros = take(32768);   // never written after the arena is cleared
     L.off_stepin = take(3 * FV_MAX_TREE * 4);
@@ -484,7 +490,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         ga.tickets = c->at<int>(ly.off_tickets); ga.zeros = c->at<uint4>(ly.off_zeros);
         ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax; ga.aligned = p.aligned;
         ga.tab_u0 = c->at<int>(p.off_tab); ga.tab_g0 = ga.tab_u0 + p.G + 1; ga.tab_cf = ga.tab_g0 + p.G; ga.tab_cl = ga.tab_cf + p.NG;
-        ga.fix_groups = ga.tab_cl + p.NG; ga.n_fix = p.n_fix; ga.rinv_out = c->at<float>(ly.off_rinv);
+        ga.fix_groups = (const int4*)(ga.tab_u0 + (((size_t)2 * p.G + 1 + 2 * p.NG + 3) & ~(size_t)3)); ga.n_fix = p.n_fix; ga.rinv_out = c->at<float>(ly.off_rinv);
         ga.T = T; ga.n_strips = p.n_strips;
         ga.ssq_in = c->at<float>(ly.off_ssq); ga.n_ssq = h / 32; ga.inv_h = 1.f / (float)h; ga.eps = cf.rms_eps;
         return ga;

@@ -125,7 +125,7 @@ struct GemmArgs {
     // the whole K range only stores its partial tiles, and k_gemm_fix, launched right behind, reduces
     // the n_fix row groups that have several contributors with one wavefront per tile.
     int defer, n_fix;
-    const int* fix_groups;   // [n_fix] row groups with more than one contributor
+    const int4* fix_groups;  // [n_fix] row groups with more than one contributor: (group, first and last contributor, the first one's segment index)
     float* rinv_out;         // [Tp] RMSNorm factors handed from k_gemm to k_gemm_fix
     int T, n_strips;     // real tokens; strips that carry real rows
     int epi;             // epilogue, for bodies that choose it at run time
@@ -669,7 +669,8 @@ __global__ __launch_bounds__(256) void k_gemm_fix(GemmArgs a) {
     }
     const int tile = blockIdx.x * 4 + wave;
     if (tile >= a.n_fix * R * TB) return;
-    const int gi = a.fix_groups[tile / (R * TB)];
+    const int4 rec = a.fix_groups[tile / (R * TB)];   // one load: nothing else stands between kernel entry and the partial loads
+    const int gi = rec.x, c_first = rec.y, c_last = rec.z, seg_first = rec.w;
     const int r = (tile / TB) % R, tb = tile % TB;
     const int strip = gi * R + r;
     if (strip >= a.n_strips) return;
@@ -677,8 +678,6 @@ __global__ __launch_bounds__(256) void k_gemm_fix(GemmArgs a) {
     bool have = false;
     if constexpr (EPI == EPI_RESID) { resid_preload(a, Tp, strip, tb, lane, pre); have = true; }
     if constexpr (EPI == EPI_QKV) have = rope_preload<D>(a, strip, tb, lane, pre);
-    const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
-    const int seg_first = gi - a.tab_g0[c_first];   // every later contributor starts inside the group: index 0
     const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
     float acc[16];
 #pragma unroll
