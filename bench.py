@@ -218,8 +218,25 @@ def main():
     for _ in range(args.warmup):
         res = step()
     a, acc, nxt = res if args.warmup else step()
-    # losslessness at full size: the planted greedy path is accepted, nothing past it
-    assert a >= args.plant and list(acc[:args.plant]) == greedy[:args.plant], (a, acc, greedy)
+    # losslessness at full size: the planted greedy path (the device's own one-token-at-a-time choices)
+    # is accepted.  The one-row and the T-row launch configurations round differently, so on a random
+    # model in bf16 they may pick different tokens at a top-2 near-tie; that is accepted only if the row
+    # that decided really is one (gap below the depth-scaled logits tolerance), and it is reported.
+    n_ok = min(int(a), args.plant)
+    assert list(acc[:n_ok]) == greedy[:n_ok], (a, acc, greedy)
+    near_tie_at = None
+    if a < args.plant:
+        node = 0
+        for tk in acc[:a]:
+            node = next(j for j in range(1, T) if int(parent[j]) == node and int(tokens[j]) == int(tk))
+        row = np.asarray(gpu.logits(T)[node], dtype=np.float64)
+        top2 = np.argsort(row)[-2:]
+        gap = (row[top2[1]] - row[top2[0]]) / np.max(np.abs(row))
+        tol = 2e-2 * max(1.0, (shape.n_layers / 4.0) ** 0.5)
+        assert int(greedy[a]) in (int(top2[0]), int(top2[1])) and gap < tol, (a, acc, greedy, gap)
+        near_tie_at = int(a)
+        log(f"planted path accepted up to depth {a} of {args.plant}: top-2 near-tie at the next node (relative gap {gap:.2e}); "
+            f"the one-row and the {T}-row steps chose differently")
 
     torch.cuda.synchronize()
     dev_ms = []
@@ -275,7 +292,8 @@ def main():
         "config": {"workload": f"{shape.name}-shape random-init decoder ({shape.n_layers} layers, hidden {shape.hidden}, "
                                f"{shape.n_q_heads}q/{shape.n_kv_heads}kv heads x {shape.head_dim}, FFN {shape.ffn}, vocab {shape.vocab}), "
                                f"prefix {L}, {T}-node draft tree (branching {branching}, planted greedy path {args.plant})",
-                   "prefix_len": L, "tree_nodes": T, "accepted_len": int(a), "batch": 1},
+                   "prefix_len": L, "tree_nodes": T, "accepted_len": int(a), "batch": 1,
+                   **({"near_tie_after_depth": near_tie_at} if near_tie_at is not None else {})},
         "latency_us": ms_per_step * 1e3,
         "device_ms_per_step": {"median": float(np.median(dev_ms)), "p10": float(np.percentile(dev_ms, 10)),
                                "p90": float(np.percentile(dev_ms, 90))},
