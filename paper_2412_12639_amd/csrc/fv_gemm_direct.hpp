@@ -296,15 +296,18 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         // wavefront t < NT sums tile t = (strip r of the row group, token block tb) over the four
         // wavefronts, in wavefront order
         const int strip = gi * RS + wave / TB, tb_ = wave % TB;
-        const float* slot0 = red + lane;
+        const float4* slot0 = (const float4*)red + lane;
         float r[16];
         if (wave < NT) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float sum = slot0[((size_t)(0 * NT + wave) * 16 + i) * 64];
+            for (int q = 0; q < 4; ++q) {
+                float4 sum = slot0[((size_t)(0 * NT + wave) * 4 + q) * 64];
 #pragma unroll
-                for (int w_ = 1; w_ < 4; ++w_) sum += slot0[((size_t)(w_ * NT + wave) * 16 + i) * 64];
-                r[i] = sum;
+                for (int w_ = 1; w_ < 4; ++w_) {
+                    const float4 v = slot0[((size_t)(w_ * NT + wave) * 4 + q) * 64];
+                    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                }
+                r[4 * q] = sum.x; r[4 * q + 1] = sum.y; r[4 * q + 2] = sum.z; r[4 * q + 3] = sum.w;
             }
         }
         // what the residual and the rotary epilogues read besides the GEMM result is requested
@@ -392,11 +395,13 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
             FV_DSTAGE(2)
         }
         // this wavefront's sums of segment s (zeros if none of its stages were ours) into LDS
-        float* my = red + (size_t)wave * NT * 1024 + lane;
+        // (16 bytes per lane and access: [wavefront][tile][register quad][lane])
+        float4* my = (float4*)red + (size_t)wave * NT * 256 + lane;
 #pragma unroll
         for (int t_ = 0; t_ < NT; ++t_)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) my[(t_ * 16 + i) * 64] = acc[t_][i];
+            for (int q = 0; q < 4; ++q)
+                my[(t_ * 4 + q) * 64] = make_float4(acc[t_][4 * q], acc[t_][4 * q + 1], acc[t_][4 * q + 2], acc[t_][4 * q + 3]);
         if (s == 0) { FV_TS(6) }
         finish_segment(s);
     }
