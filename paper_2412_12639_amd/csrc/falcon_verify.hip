@@ -418,7 +418,7 @@ int launch_persistent(fv_ctx* c, int T, int Tp, int L) {
     pa.rot = c->arena + ly.off_rot; pa.rot_stride = ly.rot_stride;
     pa.o_xa = ly.o_xa; pa.o_xm = ly.o_xm; pa.o_xba = ly.o_xba; pa.o_xbm = ly.o_xbm; pa.o_ssqa = ly.o_ssqa; pa.o_ssqm = ly.o_ssqm;
     pa.o_q = ly.o_q; pa.o_attn = ly.o_attn; pa.o_act = ly.o_act;
-    pa.part = c->at<float>(ly.off_part); pa.tickets = c->at<int>(ly.off_tickets); pa.zeros = c->at<uint4>(ly.off_zeros);
+    pa.part = c->at<float>(ly.off_part); pa.part_bytes = (unsigned)ly.part_bytes; pa.tickets = c->at<int>(ly.off_tickets); pa.zeros = c->at<uint4>(ly.off_zeros);
     pa.attn_part = c->at<float>(ly.off_apart); pa.attn_tickets = c->at<int>(ly.off_atick);
     pa.attn_ks = attn_key_split(cf.n_q_heads * (Tp / 32), L + T, 256);
     pa.bar = c->at<unsigned>(ly.off_bar); pa.gen0 = c->bar_gen; pa.err = c->at<int>(ly.off_err);

@@ -321,12 +321,25 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         if (qkv && mine_out) have_pre = rope_preload<D>(a, strip, tb_, lane, pre);
         bool finish = (nb == a.NB);   // the whole K range was ours: straight to the epilogue
         if (!finish) {
-            // partial tile out with agent-scope atomic stores (write-through: partials and tickets
-            // cross XCDs whose L2s are not coherent), acknowledged before the ticket is drawn
+            // partial tile out with write-through stores (partials and tickets cross XCDs whose L2s
+            // are not coherent), acknowledged before the ticket is drawn.  128-bit accesses through a
+            // raw buffer descriptor over the partial area (the agent-scope policy bit of the atomics;
+            // addresses bounds-checked in hardware), layout per tile [4 register quads][64 lanes][4]:
+            // four requests per tile, so the tiles of four contributors fit in flight at once.
+            constexpr int SC1 = 16;
+            const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
+            auto tile_ofs = [&](int wg_, int seg_) -> unsigned {
+                return ((unsigned)((wg_ * a.segmax + seg_) * NT + wave) * 1024u + (unsigned)lane * 4u) * 4u;
+            };
             if (wave < NT) {
-                float* pp = a.part + (((size_t)wg * a.segmax + s) * NT + wave) * 1024 + lane;
+                const unsigned o = tile_ofs(wg, s);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) __hip_atomic_store(pp + i * 64, r[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int q = 0; q < 4; ++q) {
+                    u32x4 v;
+                    v.x = __float_as_uint(r[4 * q]); v.y = __float_as_uint(r[4 * q + 1]);
+                    v.z = __float_as_uint(r[4 * q + 2]); v.w = __float_as_uint(r[4 * q + 3]);
+                    __builtin_amdgcn_raw_buffer_store_b128(v, prs, o + q * 1024u, 0, SC1);
+                }
             }
             const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
             // Segment index of this row group inside a contributor's partial area: the ranges are
@@ -343,21 +356,25 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
                 if (wave < NT) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) r[i] = 0.f;
-                    for (int c0 = c_first; c0 <= c_last; c0 += 2) {   // ascending order, two tiles in flight
-                        float v[2][16];
+                    for (int c0 = c_first; c0 <= c_last; c0 += 4) {   // ascending order, four tiles in flight
+                        u32x4 v[4][4];
 #pragma unroll
-                        for (int k = 0; k < 2; ++k) {
+                        for (int k = 0; k < 4; ++k) {
                             const int c = (c0 + k <= c_last) ? c0 + k : c_last;
-                            const int cseg = (c == c_first) ? seg_first : 0;
-                            const float* cp = a.part + (((size_t)c * a.segmax + cseg) * NT + wave) * 1024 + lane;
+                            const unsigned o = tile_ofs(c, (c == c_first) ? seg_first : 0);
 #pragma unroll
-                            for (int i = 0; i < 16; ++i) v[k][i] = __hip_atomic_load(cp + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            for (int q = 0; q < 4; ++q) v[k][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + q * 1024u, 0, SC1);
                         }
 #pragma unroll
-                        for (int k = 0; k < 2; ++k) {
+                        for (int k = 0; k < 4; ++k) {
                             const float m = (c0 + k <= c_last) ? 1.f : 0.f;
 #pragma unroll
-                            for (int i = 0; i < 16; ++i) r[i] += m * v[k][i];
+                            for (int q = 0; q < 4; ++q) {
+                                r[4 * q] += m * __uint_as_float(v[k][q].x);
+                                r[4 * q + 1] += m * __uint_as_float(v[k][q].y);
+                                r[4 * q + 2] += m * __uint_as_float(v[k][q].z);
+                                r[4 * q + 3] += m * __uint_as_float(v[k][q].w);
+                            }
                         }
                     }
                 }

@@ -32,7 +32,7 @@ struct PersistArgs {
     const uint64_t* mask;
     // rotating activations: one slot per layer (+1), offsets of each buffer inside a slot
     char* rot; size_t rot_stride, o_xa, o_xm, o_xba, o_xbm, o_ssqa, o_ssqm, o_q, o_attn, o_act;
-    float* part; int* tickets; const uint4* zeros;
+    float* part; unsigned part_bytes; int* tickets; const uint4* zeros;
     float* attn_part; int* attn_tickets; int attn_ks;
     unsigned* bar;            // [0] release word, slots at bar[64 + 32*b]
     unsigned gen0;            // barrier generation before this launch
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256, 1) void k_step_persistent(PersistArgs a) {
         const PersistGemm& p = a.g[which];
         GemmArgs ga;
         ga.Wt = (const uint4*)(a.w_layers + (size_t)l * a.layer_w_bytes + a.off_w[which]);
-        ga.part = a.part; ga.tickets = a.tickets; ga.zeros = a.zeros;
+        ga.part = a.part; ga.part_bytes = a.part_bytes; ga.tickets = a.tickets; ga.zeros = a.zeros;
         ga.NG = p.NG; ga.NB = p.NB; ga.G = p.G; ga.segmax = p.segmax;
         ga.tab_u0 = p.tab; ga.tab_g0 = p.tab + p.G + 1; ga.tab_cf = ga.tab_g0 + p.G; ga.tab_cl = ga.tab_cf + p.NG;
         ga.T = a.T; ga.n_strips = p.n_strips;
