@@ -999,12 +999,24 @@ __global__ __launch_bounds__(256) void k_argmax(ArgmaxArgs a) {
     const float* row = a.logits + (size_t)t * a.Vpad;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int v0 = tid * 4; v0 < a.V; v0 += 256 * 4) {
-        const float4 x = *(const float4*)(row + v0);
-        const float xs[4] = {x.x, x.y, x.z, x.w};
+    // eight 16-byte loads in flight per thread (the row is a latency chain otherwise: one load per
+    // trip of a loop the compiler does not pipeline); indices past Vpad are not touched, values
+    // between V and Vpad are skipped
+    for (int v0 = tid * 4; v0 < a.V; v0 += 8 * 256 * 4) {
+        float4 x[8];
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (v0 + c < a.V) argmax_combine(bv, bi, xs[c], v0 + c);
+        for (int k = 0; k < 8; ++k) {
+            const int v = v0 + k * 256 * 4;
+            x[k] = (v < a.V) ? *(const float4*)(row + v) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int v = v0 + k * 256 * 4;
+            const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (v + c < a.V) argmax_combine(bv, bi, xs[c], v + c);
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
