@@ -467,7 +467,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         ia.tok_in = c->at<int32_t>(ly.off_stepin); ia.cap = FV_MAX_TREE; ia.T = T; ia.Tp = Tp; ia.L = L; ia.half_d = D / 2;
         ia.log2_base = std::log2((double)cf.rope_base);
         ia.mask = c->at<uint64_t>(ly.off_mask); ia.pos = c->at<int32_t>(ly.off_pos); ia.rope_cs = c->at<float2>(ly.off_rope);
-        hipLaunchKernelGGL(k_ingest, dim3(1), dim3(256), 0, st, ia);
+        hipLaunchKernelGGL(k_ingest, dim3((Tp + 3) / 4), dim3(256), 0, st, ia);
         EmbedArgs ea;
         ea.table = c->at<void>(ly.off_embed); ea.tok = c->at<int32_t>(ly.off_stepin); ea.gain = c->gain(0);
         // the persistent kernel reads layer 0's slot of its rotating buffers

@@ -33,10 +33,13 @@ struct IngestArgs {
 #endif
 
 __global__ __launch_bounds__(256) void k_ingest(IngestArgs a) {
+    // one workgroup per four rows: their ancestor masks (a short chain of dependent loads each) and
+    // their rows of the rotary table (double-precision sincos, one or two entries per thread)
     const int tid = threadIdx.x;
     const int32_t* parent = a.tok_in + a.cap;
     const int32_t* depth = a.tok_in + 2 * a.cap;
-    for (int i = tid; i < a.Tp; i += 256) {
+    const int t0 = blockIdx.x * 4, t1 = (t0 + 4 < a.Tp) ? t0 + 4 : a.Tp;
+    for (int i = t0 + tid; i < t1; i += 256) {
         uint64_t m[4] = {0, 0, 0, 0};
         int p = 0;
         if (i < a.T) {
@@ -50,8 +53,8 @@ __global__ __launch_bounds__(256) void k_ingest(IngestArgs a) {
         for (int w = 0; w < 4; ++w) a.mask[i * 4 + w] = m[w];
         a.pos[i] = p;
     }
-    const int n = a.Tp * a.half_d;
-    for (int e = tid; e < n; e += 256) {
+    const int n = t1 * a.half_d;
+    for (int e = t0 * a.half_d + tid; e < n; e += 256) {
         const int t = e / a.half_d, i = e % a.half_d;
         const int p = (t < a.T) ? a.L + depth[t] : 0;
         // angle = pos * base^(-2i/d), d = 2*half_d
