@@ -786,11 +786,18 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
         for (int j = 0; j < DB * NQ; ++j) vt[j] = vp[j * 64];
     };
     auto use_block = [&](const uint4 (&kt)[NF], const uint4 (&vt)[DB * NQ], int kb) {
-        floatx16 s;
+        // two accumulation chains (a dependent MFMA waits ~50 cycles for its predecessor, two
+        // interleaved chains issue back to back), added at the end
+        floatx16 s, s1;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.f;
+        for (int i = 0; i < 16; ++i) { s[i] = 0.f; s1[i] = 0.f; }
 #pragma unroll
-        for (int fr = 0; fr < NF; ++fr) s = Tr<EL>::mma(kt[fr], qf[fr], s);
+        for (int fr = 0; fr < NF; fr += 2) {
+            s = Tr<EL>::mma(kt[fr], qf[fr], s);
+            s1 = Tr<EL>::mma(kt[fr + 1], qf[fr + 1], s1);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] += s1[i];
 
         // Visibility of the block's 32 keys for this lane's node as one 32-bit word (bit j: key
         // kb*32 + j): prefix keys are visible to every node, a tree key n only if bit n of the node's
