@@ -33,30 +33,18 @@ compaction against a fresh prefill of the extended sequence.
 
 Readings where the paper is silent are listed with each function.
 
-Precision.  The paper states none; the default is fp64 throughout.  `Oracle(storage="bf16")`
-is the same computation with the STORAGE FORMATS of the bf16 configuration written in: every
-tensor that such a configuration keeps in bf16 (the input of each weight multiplication, the
-rotated queries and keys, the values, i.e. the K/V cache, and the attention probabilities that
-multiply the values) is rounded to bf16 (round to nearest even) at the point where it is
-stored; all arithmetic stays in the working precision.  It exists for deep models, where the
-rounding noise of those formats alone (about 2^-9 relative per stored tensor, adding in
-quadrature over ~9 tensors per layer) exceeds the tolerance that is demanded of shallow ones;
-pinned in tests/test_oracle_pins.py (rounding against a library conversion; storage=None
-unchanged; exactly representable data unaffected).
+Precision.  The paper states none; the default working precision is fp64 (`dtype`), and
+nothing in this file rounds to a narrower format.  Full-size test cases pass dtype=np.float32
+to bound the run time; that moves the logits by about 1e-6 of a row's maximum.
+
+Pins added with the acceptance rule as a function of its own (`greedy_accept`): the parent-
+pointer walk on hand-made trees, chains, ties and empty acceptance, and invariance under
+relabelling; `top2_margin` against a sorted array.
 """
 import numpy as np
 
 
 # ----------------------------------------------------------------------------- helpers
-
-def round_bf16(x):
-    """Round to the nearest bf16 value, ties to even, through fp32 (the value is first an fp32
-    number, as on a device that computes in fp32); returned in x's own dtype."""
-    a = np.ascontiguousarray(x, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
-    return u.astype(np.uint32).view(np.float32).astype(np.asarray(x).dtype)
-
 
 def _up(w, dtype):
     """Weights arrive as float32 or as bf16 bit patterns (uint16); both are widened
@@ -184,15 +172,44 @@ class TreeVerifyError(ValueError):
     pass
 
 
+def greedy_accept(tokens, parent, depth, argmax, L):
+    """The acceptance and compaction rule of one verification step, as a function of the tree
+    and of the target's greedy choice at every node (section "Custom-Designed Decoding Tree":
+    candidates are checked by the LLM in the SpecInfer manner and only what it validates is
+    kept; Experiments, "Models and Tasks": temperature 0).
+
+    The root is accepted; a child is accepted iff its parent is accepted and its token is the
+    target's argmax at the parent.  The deepest accepted node wins (reading: the lowest index
+    among equally deep ones).  Returns a dict:
+      accepted_len a   number of accepted draft nodes (= depth of the best node)
+      path [a+1]       tree indices root .. best, found by walking parent pointers
+      accepted_tokens  tokens of path[1:]
+      next_token       the target's choice after the best node (the bonus token)
+      src_slot / dst_slot [a+1]   compaction: the K/V of path node j goes to cache slot L + j
+    """
+    T = len(tokens)
+    acc = np.zeros(T, dtype=bool)
+    acc[0] = True
+    for i in range(1, T):
+        acc[i] = acc[parent[i]] and int(tokens[i]) == int(argmax[parent[i]])
+    best = 0
+    for i in range(T):  # deepest accepted node, lowest index among equals
+        if acc[i] and depth[i] > depth[best]:
+            best = i
+    path = root_path(parent, best)
+    a = int(depth[best])
+    return dict(accepted_len=a, path=np.array(path, dtype=np.int32),
+                accepted_tokens=np.array([tokens[j] for j in path[1:]], dtype=np.int32),
+                next_token=int(argmax[best]),
+                src_slot=np.array(path, dtype=np.int32),
+                dst_slot=(L + np.arange(a + 1)).astype(np.int32))
+
+
 class Oracle:
     """prefill / verify_tree with a per-layer K/V cache (K stored after rotation)."""
 
-    def __init__(self, shape, weights, max_seq, dtype=np.float64, storage=None):
-        if storage not in (None, "bf16"):
-            raise ValueError("storage must be None or 'bf16'")
+    def __init__(self, shape, weights, max_seq, dtype=np.float64):
         self.s, self.w, self.dtype = shape, weights, dtype
-        self.st = round_bf16 if storage == "bf16" else (lambda t: t)
-        self.storage = storage
         s = shape
         self.K = np.zeros((s.n_layers, max_seq, s.n_kv_heads, s.head_dim), dtype=dtype)
         self.V = np.zeros_like(self.K)
@@ -200,57 +217,43 @@ class Oracle:
         self.pending = None  # token produced last, not yet in the cache (the next root)
 
     # -- one decoder pass over `n` new rows; row i attends cache slots [0, L) plus the
-    #    new rows listed in visible[i] (indices into the new rows, in any order)
+    #    new rows listed in visible[i] (indices into the new rows, in any order).
+    #    visible=None means the causal case visible[i] = [0..i] (a prompt), which is written
+    #    with a lower-triangular mask instead of a Python loop over rows: same sums.
     def _forward_rows(self, tokens, pos, visible):
         s, dt, L = self.s, self.dtype, self.L
         n = len(tokens)
         x = _up(self.w["embed"], dt)[np.asarray(tokens)]
         newK = np.zeros((s.n_layers, n, s.n_kv_heads, s.head_dim), dtype=dt)
         newV = np.zeros_like(newK)
-        grp = s.n_q_heads // s.n_kv_heads
-        st = self.st
+        scale = 1.0 / np.sqrt(s.head_dim)
         for l in range(s.n_layers):
             W = lambda k: self.w[f"l{l}.{k}"]
-            xn, post = self._norm_in(x, W("g_attn").astype(dt))
-            q = st(rope((linear(xn, W("wq"), dt) * post).reshape(n, s.n_q_heads, s.head_dim), pos, s.rope_base))
-            k = st(rope((linear(xn, W("wk"), dt) * post).reshape(n, s.n_kv_heads, s.head_dim), pos, s.rope_base))
-            v = st((linear(xn, W("wv"), dt) * post).reshape(n, s.n_kv_heads, s.head_dim))
+            xn = rmsnorm(x, W("g_attn").astype(dt), s.rms_eps)
+            q = rope(linear(xn, W("wq"), dt).reshape(n, s.n_q_heads, s.head_dim), pos, s.rope_base)
+            k = rope(linear(xn, W("wk"), dt).reshape(n, s.n_kv_heads, s.head_dim), pos, s.rope_base)
+            v = linear(xn, W("wv"), dt).reshape(n, s.n_kv_heads, s.head_dim)
             newK[l], newV[l] = k, v
             att = np.zeros((n, s.n_q_heads, s.head_dim), dtype=dt)
-            for i in range(n):
-                vis = visible[i]
-                keys = np.concatenate([self.K[l, :L], k[vis]], axis=0)   # [m, Hkv, d]
-                vals = np.concatenate([self.V[l, :L], v[vis]], axis=0)
-                # query head qh uses KV head qh // grp  (== floor(qh*Hkv/Hq))
-                kq = np.repeat(keys, grp, axis=1)                         # [m, Hq, d]
-                vq = np.repeat(vals, grp, axis=1)
-                sc = np.einsum("hd,mhd->hm", q[i], kq) / np.sqrt(s.head_dim)
-                if self.storage is None:
-                    p = softmax_lastaxis(sc)
-                    att[i] = np.einsum("hm,mhd->hd", p, vq)
+            for qh in range(s.n_q_heads):
+                kh = _kv_head_of(qh, s)
+                if visible is None:
+                    keys = np.concatenate([self.K[l, :L, kh], k[:, kh]], axis=0)      # [L + n, d]
+                    vals = np.concatenate([self.V[l, :L, kh], v[:, kh]], axis=0)
+                    sc = q[:, qh] @ keys.T * scale                                    # [n, L + n]
+                    seen = np.concatenate([np.ones((n, L), dtype=bool), np.tril(np.ones((n, n), dtype=bool))], axis=1)
+                    att[:, qh] = softmax_lastaxis(np.where(seen, sc, -np.inf)) @ vals
                 else:
-                    # stored probabilities are the un-normalised exp(s - max); the sum that
-                    # normalises them is taken before they are rounded
-                    e = np.exp(sc - np.max(sc, axis=-1, keepdims=True))
-                    att[i] = np.einsum("hm,mhd->hd", st(e), vq) / np.sum(e, axis=-1, keepdims=True)
-            x = x + linear(st(att.reshape(n, -1)), W("wo"), dt)
-            xn, post = self._norm_in(x, W("g_mlp").astype(dt))
-            a = silu(linear(xn, W("wg"), dt) * post) * (linear(xn, W("wu"), dt) * post)
-            x = x + linear(st(a), W("wd"), dt)
-        xn, post = self._norm_in(x, self.w["g_final"].astype(dt))
+                    for i in range(n):
+                        keys = np.concatenate([self.K[l, :L, kh], k[visible[i], kh]], axis=0)
+                        vals = np.concatenate([self.V[l, :L, kh], v[visible[i], kh]], axis=0)
+                        att[i, qh] = softmax_lastaxis(keys @ q[i, qh] * scale) @ vals
+            x = x + linear(att.reshape(n, -1), W("wo"), dt)
+            xn = rmsnorm(x, W("g_mlp").astype(dt), s.rms_eps)
+            x = x + linear(silu(linear(xn, W("wg"), dt)) * linear(xn, W("wu"), dt), W("wd"), dt)
         # features: what the LM head consumes (the last layer's output after the final norm)
         self.last_hidden = rmsnorm(x, self.w["g_final"].astype(dt), s.rms_eps)
-        return linear(xn, self.w["lm_head"], dt) * post, newK, newV
-
-    def _norm_in(self, x, gain):
-        """RMSNorm as the input of a weight multiplication: returns (input, factor) with
-        norm(x) W^T == (input W^T) * factor.  Default: (rmsnorm(x), 1).  With bf16 storage the
-        stored tensor is x * gain (rounded), and the per-row factor 1/sqrt(mean(x^2) + eps)
-        multiplies the product, which is the same thing in exact arithmetic."""
-        if self.storage is None:
-            return rmsnorm(x, gain, self.s.rms_eps), 1.0
-        rinv = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + self.s.rms_eps)
-        return self.st(x * gain), rinv
+        return linear(self.last_hidden, self.w["lm_head"], dt), newK, newV
 
     def prefill(self, tokens):
         """Run the prompt, fill cache slots 0..n-1, return the greedy next token (the
@@ -259,8 +262,7 @@ class Oracle:
         if n < 1 or n > self.K.shape[1]:
             raise TreeVerifyError("bad prompt length")
         self.L = 0
-        visible = [list(range(i + 1)) for i in range(n)]
-        logits, newK, newV = self._forward_rows(tokens, np.arange(n), visible)
+        logits, newK, newV = self._forward_rows(tokens, np.arange(n), None)
         self.K[:, :n], self.V[:, :n] = newK, newV
         self.L = n
         self.pending = first_argmax(logits[-1])
@@ -291,56 +293,48 @@ class Oracle:
         if int(tokens[0]) != int(pending):
             raise TreeVerifyError("root mismatch")
 
+    def tree_logits(self, tokens, parent, depth):
+        """Logits [T, V] of every node and the K/V the target computes for it ([NL, T, Hkv, d]
+        each), without touching the state: each node sees the committed prefix and the nodes on
+        its own root path, found by walking parent pointers; its position is prefix length +
+        depth."""
+        visible = [root_path(parent, i) for i in range(len(tokens))]
+        return self._forward_rows(tokens, self.L + np.asarray(depth), visible)
+
     def verify_tree(self, tokens, parent, depth):
         """One verification step.  Returns a dict with
-        logits [T,V], argmax [T], mask [T,4] u64, accepted_len a, accepted_tokens [a],
-        next_token, path [a+1] (tree indices root..best), src_slot / dst_slot [a+1],
-        features [a+1, hidden]: the LM head's input of every path node, recorded with the
-        accepted tokens for the next drafting round (section "Custom-Designed Decoding Tree";
-        reading: after the final norm, i.e. exactly what the shared LM head consumes)."""
+        logits [T,V], argmax [T], mask [T,4] u64, the fields of greedy_accept(), tree_k / tree_v
+        (the K/V of every node), and features [a+1, hidden]: the LM head's input of every path
+        node, recorded with the accepted tokens for the next drafting round (section
+        "Custom-Designed Decoding Tree"; reading: after the final norm, i.e. exactly what the
+        shared LM head consumes)."""
         s, L = self.s, self.L
         if self.pending is None:
             raise TreeVerifyError("no prefill")
         self.check_tree(tokens, parent, depth, s.vocab, self.pending, L, self.K.shape[1])
         T = len(tokens)
-        # each node sees the committed prefix and the nodes on its own root path,
-        # found by walking parent pointers; its position is prefix length + depth
-        visible = [root_path(parent, i) for i in range(T)]
-        pos = L + np.asarray(depth)
-        logits, newK, newV = self._forward_rows(tokens, pos, visible)
+        logits, newK, newV = self.tree_logits(tokens, parent, depth)
         am = np.array([first_argmax(logits[i]) for i in range(T)], dtype=np.int32)
-        # greedy acceptance: the root always; a child iff parent accepted and token
-        # equals the parent's argmax
-        acc = np.zeros(T, dtype=bool)
-        acc[0] = True
-        for i in range(1, T):
-            acc[i] = acc[parent[i]] and int(tokens[i]) == int(am[parent[i]])
-        best = 0
-        for i in range(T):  # deepest accepted node, lowest index among equals
-            if acc[i] and depth[i] > depth[best]:
-                best = i
-        path = root_path(parent, best)
-        a = int(depth[best])
-        accepted_tokens = np.array([tokens[j] for j in path[1:]], dtype=np.int32)
-        next_token = int(am[best])
-        # compaction: the K/V of path node j goes to cache slot L + j
-        src = np.array(path, dtype=np.int32)
-        dst = L + np.arange(a + 1, dtype=np.int32)
-        for j in range(a + 1):
-            self.K[:, dst[j]] = newK[:, src[j]]
-            self.V[:, dst[j]] = newV[:, src[j]]
-        self.L = L + a + 1
-        self.pending = next_token
-        return dict(logits=logits, argmax=am, mask=ancestor_mask(parent), accepted_len=a,
-                    accepted_tokens=accepted_tokens, next_token=next_token,
-                    path=src, src_slot=src, dst_slot=dst, tree_k=newK, tree_v=newV,
-                    features=self.last_hidden[src].copy())
+        out = greedy_accept(tokens, parent, depth, am, L)
+        self.commit(out, newK, newV)
+        out.update(logits=logits, argmax=am, mask=ancestor_mask(parent), tree_k=newK, tree_v=newV,
+                   features=self.last_hidden[out["path"]].copy())
+        return out
+
+    def commit(self, decision, newK, newV):
+        """Compaction and state update: the K/V of path node j goes to cache slot L + j, the
+        committed length grows by accepted_len + 1 and the bonus token becomes the next root."""
+        for src, dst in zip(decision["src_slot"], decision["dst_slot"]):
+            self.K[:, dst] = newK[:, src]
+            self.V[:, dst] = newV[:, src]
+        self.L = self.L + decision["accepted_len"] + 1
+        self.pending = decision["next_token"]
 
     def rollback(self, new_len, pending):
         self.L, self.pending = int(new_len), int(pending)
 
 
 def top2_margin(row):
-    """Gap between the largest and second-largest logit of a row."""
+    """Gap between the largest and second-largest logit of a row (0 if the maximum is attained twice)."""
     part = np.partition(row, -2)
     return float(part[-1] - part[-2])

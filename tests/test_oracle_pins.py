@@ -363,72 +363,6 @@ def test_bf16_weights_are_consumed_bit_exactly():
     assert np.array_equal(fo.causal_forward(s16, w16, toks), fo.causal_forward(fi.SHAPES["tiny"], w32, toks))
 
 
-# ---- bf16 storage model of the oracle (deep bf16 configurations)
-
-def test_round_bf16_matches_library_conversion():
-    """Round-to-nearest-even to bf16, against torch's conversion: random values over many binades,
-    exact ties in both directions, signed zeros, values that round up into the next binade."""
-    rng = np.random.default_rng(0)
-    x = (rng.standard_normal(20000) * np.exp(rng.uniform(-30, 30, 20000))).astype(np.float32)
-    ties = np.array([0x3F808000, 0x3F818000, 0xBF808000, 0xBF818000, 0x3FFF8000, 0x3FFFFFFF, 0x00000000, 0x80000000,
-                     0x3F807FFF, 0x3F808001], dtype=np.uint32).view(np.float32)
-    x = np.concatenate([x, ties])
-    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
-    got = fo.round_bf16(x)
-    assert got.dtype == np.float32 and np.array_equal(got.view(np.uint32), ref.view(np.uint32))
-    got64 = fo.round_bf16(x.astype(np.float64))
-    assert got64.dtype == np.float64 and np.array_equal(got64, ref.astype(np.float64))
-    # the two tie cases by hand: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> even mantissa (1.0);
-    # 1 + 3*2^-8 is halfway between 1 + 2^-7 and 1 + 2^-6 -> even mantissa (1 + 2^-6)
-    assert fo.round_bf16(np.float32(1 + 2.0 ** -8)) == 1.0
-    assert fo.round_bf16(np.float32(1 + 3 * 2.0 ** -8)) == np.float32(1 + 2.0 ** -6)
-
-
-def test_bf16_storage_model_keeps_the_method_invariants(small):
-    """With storage rounding written in, the step is still the same method: every node's logits are
-    those of a plain prefill (same storage model) over prefix ++ root path, and a chain tree
-    reproduces single-token decoding token for token.  And the result sits at rounding distance from
-    the fp64 one: not equal, not far."""
-    s, w, prefix = small
-    o, root, greedy, parent, depth, planted, tok = _planted_tree(s, w, prefix, 0, 16, [4, 2, 1, 1], 3)
-    ob = fo.Oracle(s, w, max_seq=len(prefix) + 40, storage="bf16")
-    rootb = ob.prefill(prefix)
-    r64 = o.verify_tree(tok, parent, depth)
-    if rootb == root:
-        rb = ob.verify_tree(tok, parent, depth)
-        err = np.max(np.abs(rb["logits"] - r64["logits"]), axis=-1) / np.max(np.abs(r64["logits"]), axis=-1)
-        assert 1e-4 < err.max() < 2e-2
-        ob.rollback(len(prefix), rootb)
-    # brute force in the same storage model
-    tok_b = np.array(tok).copy()
-    tok_b[0] = rootb
-    rb = ob.verify_tree(tok_b, parent, depth)
-    for i in (0, 3, 9, 15):
-        seq = list(prefix) + [int(tok_b[j]) for j in fo.root_path(parent, i)]
-        o2 = fo.Oracle(s, w, max_seq=len(seq) + 4, storage="bf16")
-        o2.prefill(seq)
-        ref = o2.last_logits[-1]
-        assert np.max(np.abs(rb["logits"][i] - ref)) < 1e-9 * np.max(np.abs(ref))
-    # chain == one token at a time
-    o3 = fo.Oracle(s, w, max_seq=len(prefix) + 40, storage="bf16")
-    t0 = o3.prefill(prefix)
-    seq, tk = [], t0
-    p1, d1 = fi.chain_tree(1)
-    for _ in range(4):
-        tk = o3.verify_tree(np.array([tk], dtype=np.int32), p1, d1)["next_token"]
-        seq.append(tk)
-    o3.rollback(len(prefix), t0)
-    pc, dc = fi.chain_tree(4)
-    rc = o3.verify_tree(np.array([t0] + seq[:3], dtype=np.int32), pc, dc)
-    assert rc["accepted_len"] == 3 and rc["next_token"] == seq[3]
-
-
-def test_storage_argument_is_checked(tiny):
-    s, w, prefix = tiny
-    with pytest.raises(ValueError):
-        fo.Oracle(s, w, max_seq=80, storage="fp8")
-
-
 def test_features_are_the_lm_head_input(small):
     """The features returned with the accepted tokens: multiplying them by the LM head gives the
     path nodes' logits back (closed form), and they equal the final hidden state of a from-scratch
@@ -444,3 +378,133 @@ def test_features_are_the_lm_head_input(small):
         seq = list(prefix) + [int(tok[k]) for k in fo.root_path(parent, int(node))]
         _, hid = fo.causal_forward(s, w, seq, return_hidden=True)
         assert np.max(np.abs(hid[-1] - f[j])) < 1e-10 * np.max(np.abs(hid[-1]))
+
+
+# ------------------------------------------------------------------ the acceptance rule as a pure function
+
+def _accept_by_enumeration(tokens, parent, depth, argmax):
+    """Independent statement of the rule: enumerate every root path, keep those whose every
+    non-root node carries the target's choice at its parent, take the longest (lowest end node
+    among equally long ones)."""
+    T = len(tokens)
+    best_path = [0]
+    for end in range(T):
+        path, j = [], end
+        while j >= 0:
+            path.append(j)
+            j = int(parent[j])
+        path = path[::-1]
+        ok = all(int(tokens[c]) == int(argmax[p]) for p, c in zip(path[:-1], path[1:]))
+        if ok and len(path) > len(best_path):
+            best_path = path
+    return best_path
+
+
+def test_greedy_accept_hand_made_cases():
+    """Values worked out by hand.  Tree: 0 -> (1, 2); 1 -> (3, 4); 2 -> 5; 3 -> 6."""
+    parent = np.array([-1, 0, 0, 1, 1, 2, 3], dtype=np.int32)
+    depth = np.array([0, 1, 1, 2, 2, 2, 3], dtype=np.int32)
+    tok = np.array([10, 11, 12, 13, 14, 15, 16], dtype=np.int32)
+    # target picks 11 after the root, 14 after node 1, 99 after node 4: path 0 -> 1 -> 4
+    am = np.array([11, 14, 15, 16, 99, 7, 7], dtype=np.int32)
+    r = fo.greedy_accept(tok, parent, depth, am, L=100)
+    assert r["accepted_len"] == 2 and list(r["path"]) == [0, 1, 4]
+    assert list(r["accepted_tokens"]) == [11, 14] and r["next_token"] == 99
+    assert list(r["src_slot"]) == [0, 1, 4] and list(r["dst_slot"]) == [100, 101, 102]
+    # node 5 matches its parent's choice (15) but its parent (node 2) is not accepted: not taken
+    assert 5 not in r["path"]
+    # nothing matches: only the root, bonus token = the choice at the root
+    am0 = np.array([77, 14, 15, 16, 99, 7, 7], dtype=np.int32)
+    r = fo.greedy_accept(tok, parent, depth, am0, L=5)
+    assert r["accepted_len"] == 0 and list(r["path"]) == [0] and r["next_token"] == 77
+    assert len(r["accepted_tokens"]) == 0 and list(r["dst_slot"]) == [5]
+    # a full-depth path: 0 -> 1 -> 3 -> 6
+    am3 = np.array([11, 13, 0, 16, 0, 0, 42], dtype=np.int32)
+    r = fo.greedy_accept(tok, parent, depth, am3, L=0)
+    assert r["accepted_len"] == 3 and list(r["path"]) == [0, 1, 3, 6] and r["next_token"] == 42
+    # a single node
+    r = fo.greedy_accept(np.array([3]), np.array([-1]), np.array([0]), np.array([8]), L=9)
+    assert r["accepted_len"] == 0 and r["next_token"] == 8 and list(r["dst_slot"]) == [9]
+    # equal siblings, both matching: the lower index wins
+    r = fo.greedy_accept(np.array([1, 2, 2]), np.array([-1, 0, 0]), np.array([0, 1, 1]), np.array([2, 5, 6]), L=0)
+    assert list(r["path"]) == [0, 1] and r["next_token"] == 5
+
+
+def test_greedy_accept_chains_and_random_trees_against_enumeration():
+    rng = np.random.default_rng(7)
+    # chain whose first m draft tokens are right
+    for n, m in [(1, 0), (6, 0), (6, 3), (6, 5), (40, 17)]:
+        parent, depth = fi.chain_tree(n)
+        am = rng.integers(0, 50, size=n).astype(np.int32)
+        tok = np.zeros(n, dtype=np.int32)
+        tok[1:] = am[:-1]
+        if m + 1 < n:
+            tok[m + 1] = (am[m] + 1) % 50
+        r = fo.greedy_accept(tok, parent, depth, am, L=3)
+        assert r["accepted_len"] == min(m, n - 1) and list(r["path"]) == list(range(min(m, n - 1) + 1))
+        assert r["next_token"] == am[min(m, n - 1)]
+    # random trees with a small vocabulary, so that matches are frequent and paths branch
+    for seed in range(40):
+        n = int(rng.integers(2, 60))
+        parent, depth, _ = fi.gen_tree(seed, n, [3, 3, 2, 2, 2, 1, 1, 1])
+        tok = rng.integers(0, 3, size=n).astype(np.int32)
+        am = rng.integers(0, 3, size=n).astype(np.int32)
+        r = fo.greedy_accept(tok, parent, depth, am, L=11)
+        want = _accept_by_enumeration(tok, parent, depth, am)
+        assert list(r["path"]) == want, (seed, list(r["path"]), want)
+        assert r["accepted_len"] == len(want) - 1 == depth[want[-1]]
+        assert list(r["accepted_tokens"]) == [int(tok[j]) for j in want[1:]]
+        assert r["next_token"] == am[want[-1]]
+        assert list(r["src_slot"]) == want and list(r["dst_slot"]) == list(range(11, 11 + len(want)))
+        # the set bits of the best node's ancestor mask are the path (what the library's scan uses)
+        m = fo.ancestor_mask(parent)[want[-1]]
+        assert _bits(m) == want
+
+
+def test_greedy_accept_is_invariant_under_relabelling():
+    rng = np.random.default_rng(3)
+    for seed in range(10):
+        parent, depth, _ = fi.gen_tree(seed, 30, [3, 2, 2, 2, 1, 1])
+        tok = rng.integers(0, 3, size=30).astype(np.int32)
+        am = rng.integers(0, 3, size=30).astype(np.int32)
+        # siblings distinct, so that the accepted path is unique whatever the node order
+        for i in range(1, 30):
+            sib = [j for j in range(1, i) if parent[j] == parent[i]]
+            while any(tok[j] == tok[i] for j in sib):
+                tok[i] += 3
+        r = fo.greedy_accept(tok, parent, depth, am, L=0)
+        order = sorted(range(30), key=lambda i: (depth[i], -i))
+        new_of = {old: new for new, old in enumerate(order)}
+        p2 = np.array([-1 if parent[o] < 0 else new_of[parent[o]] for o in order], dtype=np.int32)
+        r2 = fo.greedy_accept(tok[order], p2, depth[order], am[order], L=0)
+        assert list(r2["accepted_tokens"]) == list(r["accepted_tokens"]) and r2["next_token"] == r["next_token"]
+        assert [order[j] for j in r2["path"]] == list(r["path"])
+
+
+def test_top2_margin_against_sorted_array():
+    rng = np.random.default_rng(1)
+    for _ in range(20):
+        row = rng.standard_normal(int(rng.integers(2, 500)))
+        srt = np.sort(row)
+        assert fo.top2_margin(row) == float(srt[-1] - srt[-2])
+    assert fo.top2_margin(np.array([1.0, 4.0, 4.0, -2.0])) == 0.0          # maximum attained twice
+    assert fo.top2_margin(np.array([3.0, -1.0])) == 4.0
+    assert fo.top2_margin(np.array([-5.0, -7.0, -6.0])) == 1.0              # all negative
+    assert fo.top2_margin(np.array([2.0, 9.0, 9.0, 9.0])) == 0.0
+
+
+def test_verify_tree_uses_the_acceptance_function(tiny):
+    """verify_tree's decisions are greedy_accept of its own argmax; tree_logits leaves the state alone."""
+    s, w, prefix = tiny
+    o, root, greedy, parent, depth, planted, tok = _planted_tree(s, w, prefix, 0, 16, [4, 2, 1, 1], 2)
+    lg, nk, nv = o.tree_logits(tok, parent, depth)
+    assert o.L == 64 and o.pending == root
+    r = o.verify_tree(tok, parent, depth)
+    assert np.array_equal(lg, r["logits"]) and np.array_equal(nk, r["tree_k"])
+    d = fo.greedy_accept(tok, parent, depth, r["argmax"], 64)
+    for key in ("accepted_len", "next_token"):
+        assert d[key] == r[key]
+    for key in ("path", "accepted_tokens", "src_slot", "dst_slot"):
+        assert list(d[key]) == list(r[key])
+    for j, node in enumerate(r["path"]):
+        assert np.array_equal(o.K[:, 64 + j], r["tree_k"][:, node]) and np.array_equal(o.V[:, 64 + j], r["tree_v"][:, node])
