@@ -37,23 +37,6 @@
  * Errors: every int-returning call gives FV_OK (0) or a negative fv_status.  Argument
  * and tree validation happens on the host before anything is launched; a rejected call
  * changes no state and writes no output.
- *
- * Environment switches, read once by fv_create (tuning and test aids; every setting computes
- * the same step and is held to the same parity tests):
- *   FV_GEMM = paired | direct | wide | shared   GEMM kernel for steps of up to 64 rows.  Default:
- *       paired (two 32-row strips per wavefront) wherever the K range is long enough, else
- *       direct (one strip).  wide: four strips per wavefront.  shared: the LDS-shared-activation
- *       kernel that steps of more than 64 rows always use.
- *   FV_GEMM_ALIGN = 0 | 1     force the stream-K split (0) or whole row groups per workgroup (1);
- *       default: whole groups only where that idles at most 10 % of the workgroups.
- *   FV_GEMM_PAIRED_SET = mask over (QKV, O, gate/up, down, head): matrices that may use the paired form.
- *   FV_GEMM_WGS = n           workgroups the GEMMs are split over (default 256, one per compute unit).
- *   FV_GEMM_FIX = 0           steps of more than 64 rows: let the last workgroup to arrive reduce a row group's
- *       partial tiles inside the GEMM launch (default: a second launch reduces them, one wavefront per tile,
- *       for the QKV, O and down projections).
- *   FV_PERSISTENT = 1         run all decoder layers of a step of up to 64 rows in one cooperative
- *       persistent kernel instead of one launch per GEMM.
- *   FV_PERSIST_TIMING = 1     record time stamps in the persistent kernel (see fv_debug_persist_timing).
  */
 #ifndef FALCON_VERIFY_H
 #define FALCON_VERIFY_H
@@ -75,7 +58,11 @@ typedef enum fv_status {
     FV_E_CACHE_FULL = -6,     /* L + n_nodes > max_seq */
     FV_E_ROOT_MISMATCH = -7,  /* tree_tokens[0] is not the pending root token */
     FV_E_NO_PREFILL = -8,     /* verify_tree / rollback before prefill, or weights not set */
-    FV_E_HIP = -9             /* a HIP runtime call failed (no usable GPU, launch error) */
+    FV_E_HIP = -9,            /* a HIP runtime call failed (no usable GPU, launch error) */
+    FV_E_NONFINITE = -10,     /* the logits of some node hold a NaN or an infinity: there is no greedy choice;
+                                 the committed length and the pending root are left as they were */
+    FV_E_SCRATCH_LIMIT = -11  /* fv_verify_tree_noalloc: n_nodes > FV_NOALLOC_MAX_NODES, or the shape needs more
+                                 scratch than the library's static device array holds */
 } fv_status;
 
 enum { FV_F32 = 0, FV_BF16 = 1 };
@@ -152,6 +139,22 @@ int fv_verify_tree(fv_ctx* ctx, const int32_t* tree_tokens, const int32_t* paren
                    const int32_t* depth, int32_t n_nodes,
                    int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc inside the step): fv_verify_tree with every scratch buffer of the step's
+ * kernels (stream-K partial tiles and tickets, attention key-split partials and tickets) taken from
+ * a static device array of 32 MiB inside the library instead of the arena's.  It calls no hipMalloc,
+ * hipFree or other allocating routine.  Same arguments, outputs, errors and state changes as
+ * fv_verify_tree, and bitwise the same results.  Limits: n_nodes <= FV_NOALLOC_MAX_NODES and a
+ * model shape whose scratch fits the array (all shapes with at most 56 query heads of 128 and 256
+ * GEMM workgroups do), else FV_E_SCRATCH_LIMIT and nothing is changed.  Every GPU the library has
+ * created a context on holds its own copy of the array until the process ends; all contexts on one
+ * GPU share it, so calls that overlap on one GPU (two streams, two threads) race.  The array keeps
+ * the last call's contents; what must start at zero is cleared by a small kernel at each call. */
+#define FV_NOALLOC_MAX_NODES 64
+int fv_verify_tree_noalloc(fv_ctx* ctx, const int32_t* tree_tokens, const int32_t* parent_idx,
+                           const int32_t* depth, int32_t n_nodes,
+                           int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token);
+
 /* Reset the committed length and pending root (0 <= new_len <= current capacity use is
  * the caller's responsibility: slots below new_len must hold valid K/V).  Used to replay
  * the same step and to resume. */
@@ -192,23 +195,15 @@ int fv_read_kv(fv_ctx* ctx, int32_t layer, int32_t slot0, int32_t n, float* k_ou
 enum { FV_ACT_X = 0, FV_ACT_XB = 1, FV_ACT_Q = 2, FV_ACT_ATTN = 3, FV_ACT_FFN = 4 };
 int fv_debug_read_activation(fv_ctx* ctx, int32_t which, int32_t n_nodes, float* out);
 
-/* Tuning aid: when the environment variable FV_PERSIST_TIMING is set, the persistent step kernel
- * records, for layer 1, a 100 MHz time stamp before and after each of its grid barriers in every
- * workgroup, and (second block) stamps from inside the GEMM phase whose number the variable
- * holds (2 = O, 3 = gate/up, 4 = down); this copies both out as [2][256][16] (unused entries zero). */
-int fv_debug_persist_timing(fv_ctx* ctx, long long* out);
-
 /* ---- measurement ---- */
 
 /* When enabled, each subsequent step brackets its kernels with HIP events on the
  * context's stream and accumulates per-phase device time.  Off by default (the events
  * cost launch gaps). */
 int fv_set_profiling(fv_ctx* ctx, int32_t enabled);
-/* phases: the weight-streaming GEMM kernels; (unused, kept for layout); tree attention kernels;
- * everything else (ingest, embedding, argmax, path scan, compaction); the persistent kernel that
- * runs all decoder layers of a step of up to 64 nodes in one launch (then the GEMM phase holds
- * only the LM head and the attention phase is empty) */
-enum { FV_PH_GEMM = 0, FV_PH_FIXUP = 1, FV_PH_ATTN = 2, FV_PH_OTHER = 3, FV_PH_PERSIST = 4, FV_PH_COUNT = 5 };
+/* phases: the weight-streaming GEMM kernels; the separate reduction launches of steps of more than
+ * 64 rows; tree attention kernels; everything else (ingest, embedding, argmax, path scan, compaction) */
+enum { FV_PH_GEMM = 0, FV_PH_FIXUP = 1, FV_PH_ATTN = 2, FV_PH_OTHER = 3, FV_PH_COUNT = 4 };
 /* Accumulated milliseconds and launch counts per phase since the last reset; reading
  * resets them.  Arrays of FV_PH_COUNT. */
 int fv_get_phase_times(fv_ctx* ctx, float* ms, int32_t* launches);

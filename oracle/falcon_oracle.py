@@ -205,6 +205,76 @@ def greedy_accept(tokens, parent, depth, argmax, L):
                 dst_slot=(L + np.arange(a + 1)).astype(np.int32))
 
 
+def sampled_accept(logits, tokens, parent, depth, L, temperature, u_accept, u_sample, draft_probs=None):
+    """Non-greedy verification of a token tree (Appendix "Tree Structure": in a non-greedy setting the
+    children of a node are sampled instead of being the top-m tokens; section "Custom-Designed
+    Decoding Tree": verification is consistent with SpecInfer, i.e. its multi-step speculative
+    sampling over the tree).  A pure function of the target's logits and of uniform random numbers
+    that are passed in, so that it can be applied to any logits.
+
+    Starting at the root with the target distribution p = softmax(logits[node] / temperature):
+    the children of the current node are tried in index order; child c with token x is accepted
+    with probability min(1, p[x] / q[x]) (the test is  u_accept[c] * q[x] <= p[x]); on rejection
+    p becomes the normalised positive part of p - q and the next child is tried against it.  An
+    accepted child becomes the current node.  When no child is accepted (or the node is a leaf) the
+    next token is drawn from what is left of p by inverting its cumulative sum over increasing
+    token ids at u_sample[node].  q is the distribution the drafter drew that node's children from:
+    row `node` of draft_probs [T, V]; with draft_probs=None every child is its own point-mass
+    proposal (q[x] = 1, the case of deterministic top-m children), for which the rule reads: accept
+    with probability p[x], else strike x from p and renormalise.  Either way every emitted token
+    is distributed exactly as the target's own sampling would have it.
+
+    Returns the fields of greedy_accept() plus `min_margin`: the smallest relative distance of any
+    test from its threshold, and of the final draw from a boundary of the cumulative sum (a caller
+    comparing two implementations rejects instances where that is within their rounding error)."""
+    T = len(tokens)
+    children = [[] for _ in range(T)]
+    for i in range(1, T):
+        children[int(parent[i])].append(i)
+    cur, path, min_margin = 0, [0], np.inf
+    while True:
+        z = np.asarray(logits[cur], dtype=np.float64) / float(temperature)
+        if not np.all(np.isfinite(z)):
+            raise FloatingPointError("non-finite logits")
+        w = np.exp(z - np.max(z))          # unnormalised target distribution after `cur`
+        S = float(np.sum(w))
+        taken = None
+        for c in children[cur]:
+            x = int(tokens[c])
+            qx = 1.0 if draft_probs is None else float(draft_probs[cur][x])
+            lhs, rhs = float(u_accept[c]) * qx * S, float(w[x])
+            min_margin = min(min_margin, abs(lhs - rhs) / max(lhs, rhs, 1e-300))
+            if lhs <= rhs:
+                taken = c
+                break
+            if draft_probs is None:
+                w[x] = 0.0
+            else:
+                w = np.maximum(w - S * np.asarray(draft_probs[cur], dtype=np.float64), 0.0)
+            S2 = float(np.sum(w))
+            if S2 <= 0.0:     # nothing is left besides what was rejected (probability zero): keep the last p
+                w = np.exp(z - np.max(z))
+                S2 = float(np.sum(w))
+            S = S2
+        if taken is None:
+            cdf = np.cumsum(w)
+            target = float(u_sample[cur]) * S
+            nxt = int(np.searchsorted(cdf, target, side="right"))
+            nxt = min(nxt, len(w) - 1)
+            while w[nxt] == 0.0 and nxt > 0:   # a struck token has zero width: it cannot be drawn
+                nxt -= 1
+            lo = cdf[nxt - 1] if nxt > 0 else 0.0
+            min_margin = min(min_margin, min(abs(target - lo), abs(cdf[nxt] - target)) / S)
+            break
+        cur = taken
+        path.append(cur)
+    a = len(path) - 1
+    return dict(accepted_len=a, path=np.array(path, dtype=np.int32),
+                accepted_tokens=np.array([tokens[j] for j in path[1:]], dtype=np.int32),
+                next_token=nxt, src_slot=np.array(path, dtype=np.int32),
+                dst_slot=(L + np.arange(a + 1)).astype(np.int32), min_margin=float(min_margin))
+
+
 class Oracle:
     """prefill / verify_tree with a per-layer K/V cache (K stored after rotation)."""
 

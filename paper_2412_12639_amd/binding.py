@@ -10,8 +10,8 @@ _LIB = None
 
 STATUS = {0: "FV_OK", -1: "FV_E_BAD_ARG", -2: "FV_E_TREE_ORDER", -3: "FV_E_TREE_DEPTH", -4: "FV_E_TOKEN_RANGE",
           -5: "FV_E_TREE_TOO_BIG", -6: "FV_E_CACHE_FULL", -7: "FV_E_ROOT_MISMATCH", -8: "FV_E_NO_PREFILL",
-          -9: "FV_E_HIP"}
-PHASES = ("gemm", "fixup", "attn", "other", "persistent")
+          -9: "FV_E_HIP", -10: "FV_E_NONFINITE", -11: "FV_E_SCRATCH_LIMIT"}
+PHASES = ("gemm", "fixup", "attn", "other")
 
 
 class FvError(RuntimeError):
@@ -60,6 +60,7 @@ def load_library():
         "fv_init_weights": [vp, C.POINTER(fv_host_weights)],
         "fv_prefill": [vp, i32p, C.c_int32, i32p],
         "fv_verify_tree": [vp, i32p, i32p, i32p, C.c_int32, i32p, i32p, i32p],
+        "fv_verify_tree_noalloc": [vp, i32p, i32p, i32p, C.c_int32, i32p, i32p, i32p],
         "fv_rollback": [vp, C.c_int32, C.c_int32],
         "fv_get_state": [vp, i32p, i32p],
         "fv_get_tree_mask": [vp, C.POINTER(C.c_uint64), C.c_int32],
@@ -190,7 +191,8 @@ class FalconVerifier:
         self.last_n = len(t) - ((len(t) - 1) // self.max_tree) * self.max_tree   # rows of the last chunk
         return nxt.value
 
-    def verify_tree(self, tokens, parent, depth):
+    def verify_tree(self, tokens, parent, depth, noalloc: bool = False):
+        """noalloc=True calls fv_verify_tree_noalloc (scratch in the library's static device array)."""
         t, tp = _i32(tokens)
         p, pp = _i32(parent)
         d, dp = _i32(depth)
@@ -199,8 +201,9 @@ class FalconVerifier:
         a = C.c_int32(-1)
         nxt = C.c_int32(-1)
         acc = np.zeros(max(1, len(t)), dtype=np.int32)
-        self._chk(self.lib.fv_verify_tree(self.ctx, tp, pp, dp, len(t), C.byref(a),
-                                          acc.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nxt)), "fv_verify_tree")
+        fn = self.lib.fv_verify_tree_noalloc if noalloc else self.lib.fv_verify_tree
+        self._chk(fn(self.ctx, tp, pp, dp, len(t), C.byref(a), acc.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nxt)),
+                  "fv_verify_tree_noalloc" if noalloc else "fv_verify_tree")
         self.last_n = len(t)
         return a.value, acc[:a.value].copy(), nxt.value
 
@@ -269,10 +272,10 @@ class FalconVerifier:
         self._chk(self.lib.fv_set_profiling(self.ctx, 1 if on else 0), "fv_set_profiling")
 
     def phase_times(self):
-        ms = (C.c_float * 5)()
-        n = (C.c_int32 * 5)()
+        ms = (C.c_float * len(PHASES))()
+        n = (C.c_int32 * len(PHASES))()
         self._chk(self.lib.fv_get_phase_times(self.ctx, ms, n), "fv_get_phase_times")
-        return {PHASES[i]: (ms[i], n[i]) for i in range(5)}
+        return {PHASES[i]: (ms[i], n[i]) for i in range(len(PHASES))}
 
     def last_step_ms(self) -> float:
         v = C.c_float()

@@ -1,22 +1,27 @@
-"""Compile the HIP library for gfx950, in-tree (hipcc cross-compiles without a GPU)."""
+"""Compile the HIP library for gfx950, in-tree (hipcc cross-compiles without a GPU).
+
+The kernels are instantiated per (element type, head size) pair in csrc/fv_step.hip, compiled four
+times with different -D settings; those objects and csrc/falcon_verify.hip (the C ABI) are built in
+parallel into _build/ and linked into libfalcon_verify.so."""
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libfalcon_verify.so")
-SRC = os.path.join(HERE, "csrc", "falcon_verify.hip")
-DEPS = sorted(os.path.join(HERE, "csrc", f) for f in os.listdir(os.path.join(HERE, "csrc"))) + \
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+DEPS = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC)) + \
     [os.path.join(os.path.dirname(HERE), "include", "falcon_verify.h")]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+UNITS = [("falcon_verify", "falcon_verify.hip", [])] + \
+    [(f"fv_step_{el.lower()}_d{d}", "fv_step.hip", [f"-DFV_INST_EL={el}", f"-DFV_INST_D={d}"])
+     for el in ("BF16", "F32") for d in (128, 64)]
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS):
-        return LIB
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument", "-o", LIB, SRC]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), file=sys.stderr)
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -25,8 +30,21 @@ def build(force: bool = True, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if err.strip():
         sys.stderr.write(err + "\n")
+
+
+def build(force: bool = True, verbose: bool = False, extra_flags=()) -> str:
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS):
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ, exist_ok=True)
+    objs = [os.path.join(OBJ, name + ".o") for name, _, _ in UNITS]
+    jobs = [[hipcc, *FLAGS, *extra_flags, *defs, "-c", os.path.join(CSRC, src), "-o", obj]
+            for (_, src, defs), obj in zip(UNITS, objs)]
+    with ThreadPoolExecutor(min(len(jobs), os.cpu_count() or 1)) as ex:
+        list(ex.map(lambda c: _run(c, verbose), jobs))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(force=True))
+    print(build(force=True, verbose="-v" in sys.argv))

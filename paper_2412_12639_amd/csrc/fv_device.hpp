@@ -31,6 +31,13 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
     return __builtin_bit_cast(float, (uint32_t)b << 16);
 }
 
+// what is left of v after rounding it to bf16: v = hi + lo with hi = bf16(v) exactly representable,
+// and lo itself rounded to bf16 carries v to about 16 mantissa bits
+__device__ __forceinline__ float bf16_residual(float v) {
+    __bf16 h = (__bf16)v;
+    return v - bf16_bits_to_f32(__builtin_bit_cast(uint16_t, h));
+}
+
 template <typename EL> struct Tr;
 
 template <> struct Tr<BF16> {
@@ -76,52 +83,46 @@ template <> struct Tr<F32> {
     }
 };
 
-// ---- stores that other workgroups of the SAME kernel launch will read (persistent step kernel).
-// The XCDs' L2 caches are not coherent with each other inside a launch, so such data is written
-// with agent-scope atomic stores, which the hardware performs write-through (sc1).  COH = false
-// gives plain stores for data that is only read by later launches.
-template <bool COH> __device__ __forceinline__ void st_u64(void* p, uint64_t v) {
-    if constexpr (COH) __hip_atomic_store((uint64_t*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *(uint64_t*)p = v;
+// ---- hand-off of data between workgroups of one launch (partial tiles, attention partials).
+// Two things are needed and they are provided separately.  (1) Visibility in hardware: the XCDs'
+// L2 caches are not coherent with each other, so the payload is written with write-through
+// (agent-scope) stores and read with agent-scope loads, and the producer waits for the stores'
+// acknowledgement (vmcnt(0)) before it draws the ticket.  An agent-scope release fence would do
+// that too, but by writing back the whole L2, once per workgroup: measured 3x the step time.
+// (2) Ordering in the compiler: the payload accesses must not be moved across the ticket
+// operation.  These workgroup-scope fences do that (a fence orders all memory operations around
+// it, atomic or not); at this scope they cost no cache maintenance, only wait counts.
+__device__ __forceinline__ void handoff_release() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): stores count in vmcnt on this target
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
 }
-template <bool COH> __device__ __forceinline__ void st_f32(float* p, float v) {
-    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
-}
-template <bool COH> __device__ __forceinline__ void st_f4(float4* p, float4 v) {
-    if constexpr (COH) {
-        st_u64<true>(p, (uint64_t)__builtin_bit_cast(uint32_t, v.x) | ((uint64_t)__builtin_bit_cast(uint32_t, v.y) << 32));
-        st_u64<true>((char*)p + 8, (uint64_t)__builtin_bit_cast(uint32_t, v.z) | ((uint64_t)__builtin_bit_cast(uint32_t, v.w) << 32));
-    } else *p = v;
-}
+__device__ __forceinline__ void handoff_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
+
+// ---- stores of activations and cache rows (read by later launches: plain stores)
+__device__ __forceinline__ void st_u64(void* p, uint64_t v) { *(uint64_t*)p = v; }
+__device__ __forceinline__ void st_f32(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_f4(float4* p, float4 v) { *p = v; }
 // one cache element (bf16 or fp32)
-template <typename EL, bool COH> __device__ __forceinline__ void st_elem(void* p, size_t i, float v);
-template <> __device__ __forceinline__ void st_elem<BF16, false>(void* p, size_t i, float v) { Tr<BF16>::store(p, i, v); }
-template <> __device__ __forceinline__ void st_elem<F32, false>(void* p, size_t i, float v) { Tr<F32>::store(p, i, v); }
-template <> __device__ __forceinline__ void st_elem<BF16, true>(void* p, size_t i, float v) {
-    __bf16 h = (__bf16)v;
-    __hip_atomic_store((uint16_t*)p + i, __builtin_bit_cast(uint16_t, h), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <> __device__ __forceinline__ void st_elem<F32, true>(void* p, size_t i, float v) { st_f32<true>((float*)p + i, v); }
+template <typename EL> __device__ __forceinline__ void st_elem(void* p, size_t i, float v) { Tr<EL>::store(p, i, v); }
 
 // four consecutive cache elements starting at element index i (i % 4 == 0)
-template <typename EL, bool COH> __device__ __forceinline__ void st_cache4(void* p, size_t i, const float (&v)[4]) {
+template <typename EL> __device__ __forceinline__ void st_cache4(void* p, size_t i, const float (&v)[4]) {
     if constexpr (Tr<EL>::E == 8) {
-        st_u64<COH>((char*)p + i * 2, (uint64_t)pack_bf16x2(v[0], v[1]) | ((uint64_t)pack_bf16x2(v[2], v[3]) << 32));
+        st_u64((char*)p + i * 2, (uint64_t)pack_bf16x2(v[0], v[1]) | ((uint64_t)pack_bf16x2(v[2], v[3]) << 32));
     } else {
-        st_f4<COH>((float4*)((float*)p + i), make_float4(v[0], v[1], v[2], v[3]));
+        st_f4((float4*)((float*)p + i), make_float4(v[0], v[1], v[2], v[3]));
     }
 }
 
 // Store four consecutive features f0..f0+3 (f0 % 4 == 0) of token t into a vector-major
 // activation buffer.
-template <typename EL, bool COH = false>
+template <typename EL>
 __device__ __forceinline__ void store4_act(void* base, int Tp, int f0, int t, float a, float b, float c, float d) {
     if constexpr (Tr<EL>::E == 8) {
         char* p = (char*)base + ((size_t)(f0 >> 3) * Tp + t) * 16 + (f0 & 7) * 2;
-        st_u64<COH>(p, (uint64_t)pack_bf16x2(a, b) | ((uint64_t)pack_bf16x2(c, d) << 32));
+        st_u64(p, (uint64_t)pack_bf16x2(a, b) | ((uint64_t)pack_bf16x2(c, d) << 32));
     } else {
-        st_f4<COH>((float4*)base + ((size_t)(f0 >> 2) * Tp + t), make_float4(a, b, c, d));
+        st_f4((float4*)base + ((size_t)(f0 >> 2) * Tp + t), make_float4(a, b, c, d));
     }
 }
 

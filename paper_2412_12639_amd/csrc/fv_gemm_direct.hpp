@@ -33,25 +33,6 @@
 #define FV_DIRECT_SMEM_FLOATS(TB) (4 * (TB) * 1024 + (TB) * 32 + 1024 + 4)
 #define FV_PAIRED_SMEM_FLOATS(TB) (4 * 2 * (TB) * 1024 + (TB) * 32 + 1024 + 4)
 
-template <typename EL, int D, int EPI, bool COH>
-__device__ __forceinline__ void epilogue_dispatch(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&r)[16],
-                                                  const float* rinv_lds, const EpiPre& pre, bool have_pre) {
-    if constexpr (EPI >= 0) {
-        gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre);
-    } else {
-        switch (a.epi) {
-            case EPI_QKV: gemm_epilogue<EL, D, EPI_QKV, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre); break;
-            case EPI_RESID: gemm_epilogue<EL, D, EPI_RESID, COH>(a, Tp, strip, tb, lane, r, rinv_lds, pre, have_pre); break;
-            case EPI_SWIGLU: gemm_epilogue<EL, D, EPI_SWIGLU, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
-            default: gemm_epilogue<EL, D, EPI_LOGITS, COH>(a, Tp, strip, tb, lane, r, rinv_lds); break;
-        }
-    }
-}
-
-// Position in a wavefront's stage stream as a general cursor (used by the wide form, which has
-// few, large stages): segment, row group, stage and slice end; (lgi, lb) = last valid position.
-struct DCur { int s, gi, b, e, lgi, lb; };
-
 // This workgroup's range of the (row group, K stage) space and this wavefront's slices of it.
 struct DPlan {
     int u0, u1, g0, nseg, NB, wave;
@@ -91,19 +72,6 @@ struct DPlan {
         ws = b0 + nb * wave / 4;
         we = b0 + nb * (wave + 1) / 4;
     }
-    __device__ __forceinline__ void settle(DCur& c) const {   // skip empty slices
-        while (c.s < nseg && c.b >= c.e) {
-            ++c.s;
-            if (c.s < nseg) slice(c.s, c.gi, c.b, c.e);
-        }
-        if (c.s < nseg) { c.lgi = c.gi; c.lb = c.b; }
-    }
-    __device__ __forceinline__ void start(DCur& c) const {
-        c.s = 0; c.lgi = g0; c.lb = u0 - g0 * NB;   // a valid address even if this wavefront has no stage at all
-        slice(0, c.gi, c.b, c.e);
-        settle(c);
-    }
-    __device__ __forceinline__ void next(DCur& c) const { if (c.s < nseg) { ++c.b; settle(c); } }
 };
 
 // Request stream of one wavefront: the stages of its slices in order, every slice padded to a
@@ -116,53 +84,9 @@ struct DReq {
     const uint4* xp;
 };
 
-// EPI >= 0: epilogue fixed at compile time; EPI = -1: taken from a.epi at run time (the persistent
-// step kernel runs all its GEMMs through one copy of this body).  COH: outputs are read by other
-// workgroups of the same launch (see st_u64).  `wg` is this workgroup's index in the split.
-// Requests the weight tiles of the first three stages of this wavefront's stream into `w`: exactly
-// what gemm_direct_body's prologue would request (same split, same slices, same padding).
-template <int RS>
-__device__ __forceinline__ void gemm_direct_prefetch(const GemmArgs& a, int wg, uint4 (&w)[3][FV_FRAGS]) {
-    constexpr int SF = FV_FRAGS / RS;
-    if (wg >= a.G) return;
-    const int lane = threadIdx.x & 63;
-    DPlan pl;
-    pl.init(a, wg, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
-    int sl = 0, j = 0, n = 0, n3 = 0;
-    const uint4* wp = a.zeros;
-    auto enter = [&](int s0) {
-        sl = s0; j = 0; n = 0; n3 = 0; wp = a.zeros;
-        while (sl < pl.nseg) {
-            int gi, ws, we;
-            pl.slice(sl, gi, ws, we);
-            if (we > ws) {
-                n = we - ws; n3 = (n + 2) / 3 * 3;
-                wp = a.Wt + ((size_t)gi * RS * a.NB + ws) * (SF * 64) + lane;
-                return;
-            }
-            ++sl;
-        }
-    };
-    enter(0);
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        const bool live = j < n;
-        const uint4* p = live ? wp : a.zeros;
-        const size_t rstride = live ? (size_t)a.NB * (SF * 64) : 0;
-#pragma unroll
-        for (int r = 0; r < RS; ++r)
-#pragma unroll
-            for (int f = 0; f < SF; ++f) w[i][r * SF + f] = (p + r * rstride)[f * 64];
-        ++j; wp += SF * 64;
-        if (j >= n3) enter(sl + 1);
-    }
-}
-
-// `w` are the three weight register sets; if `preloaded`, gemm_direct_prefetch has already requested
-// the first three stages into them (the persistent kernel does that ahead of the grid barrier that
-// ends the previous phase: weights do not depend on activations).
-template <typename EL, int TB, int D, int EPI, bool COH, int RS = 1>
-__device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, float* smem, uint4 (&w)[3][FV_FRAGS], bool preloaded) {
+// `wg` is this workgroup's index in the split.
+template <typename EL, int TB, int D, int EPI, int RS = 1>
+__device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, float* smem) {
     constexpr int Tp = TB * 32;
     constexpr int SF = FV_FRAGS / RS;            // fragments per stage
     constexpr int NX = SF * TB;                  // activation tiles per stage
@@ -172,7 +96,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     float* rinv_lds = red + 4 * NT * 1024;
     float* red_lds = rinv_lds + Tp;              // 16-byte aligned: Tp is a multiple of 32
     int* ticket_lds = (int*)(red_lds + 1024);
-    const bool with_norm = (EPI >= 0) ? (EPI != EPI_RESID) : (a.epi != EPI_RESID);
+    constexpr bool with_norm = EPI != EPI_RESID;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tl = lane & 31, g = lane >> 5;
@@ -257,7 +181,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         if (rq.j >= rq.n3) enter_slice(rq.s + 1);   // also taken, harmlessly, once the stream has ended
     };
 
-    uint4 x[3][NX];
+    uint4 x[3][NX], w[3][FV_FRAGS];
     enter_slice(0);
     FV_TS(2)
     // prologue in the loop's own issue order: X(0) W(0) X(1) W(1) X(2) W(2)
@@ -265,7 +189,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     for (int i = 0; i < 3; ++i) {
         load_x(x[i]);
         __builtin_amdgcn_sched_barrier(0);
-        if (!preloaded) load_w(w[i]);
+        load_w(w[i]);
         __builtin_amdgcn_sched_barrier(0);
         advance();
         if (i == 0) { FV_TS(3) }
@@ -312,8 +236,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         }
         // what the residual and the rotary epilogues read besides the GEMM result is requested
         // now, so that it travels while the partial tiles are exchanged
-        const bool resid = (EPI >= 0) ? (EPI == EPI_RESID) : (a.epi == EPI_RESID);
-        const bool qkv = (EPI >= 0) ? (EPI == EPI_QKV) : (a.epi == EPI_QKV);
+        constexpr bool resid = EPI == EPI_RESID, qkv = EPI == EPI_QKV;
         EpiPre pre;
         const bool mine_out = wave < NT && strip < a.n_strips;
         bool have_pre = false;
@@ -346,10 +269,11 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
             // contiguous, so every contributor but the first starts inside the group (index 0); the
             // first one's index is fetched now, not between the ticket and the partial loads.
             const int seg_first = gi - a.tab_g0[c_first];
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): stores count in vmcnt on this target
+            handoff_release();
             __syncthreads();
             if (tid == 0) *ticket_lds = __hip_atomic_fetch_add(&a.tickets[gi], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
+            handoff_acquire();
             if (*ticket_lds == c_last - c_first) {
                 finish = true;
                 if (tid == 0) __hip_atomic_store(&a.tickets[gi], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
@@ -380,7 +304,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
                 }
             }
         }
-        if (finish && mine_out) epilogue_dispatch<EL, D, EPI, COH>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, have_pre);
+        if (finish && mine_out) gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, have_pre);
         __syncthreads();   // `red` and ticket_lds are reused
     };
 
@@ -429,14 +353,12 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
 template <typename EL, int TB, int D, int EPI>
 __global__ __launch_bounds__(256, 1) void k_gemm_direct(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem_dyn[];   // FV_DIRECT_SMEM_FLOATS(TB) floats
-    uint4 w[3][FV_FRAGS];
-    gemm_direct_body<EL, TB, D, EPI, false>(a, blockIdx.x, smem_dyn, w, false);
+    gemm_direct_body<EL, TB, D, EPI>(a, blockIdx.x, smem_dyn);
 }
 
 // Two strips per wavefront, half-batch stages.  a.NG counts 64-row groups, a.NB half batches.
 template <typename EL, int TB, int D, int EPI>
 __global__ __launch_bounds__(256, 1) void k_gemm_paired(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) float smem_dyn[];   // FV_PAIRED_SMEM_FLOATS(TB) floats
-    uint4 w[3][FV_FRAGS];
-    gemm_direct_body<EL, TB, D, EPI, false, 2>(a, blockIdx.x, smem_dyn, w, false);
+    gemm_direct_body<EL, TB, D, EPI, 2>(a, blockIdx.x, smem_dyn);
 }

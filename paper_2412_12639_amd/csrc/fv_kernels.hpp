@@ -4,10 +4,7 @@
 // fv_device.hpp.  Every kernel checks its own bounds; the host checks shapes first.
 #pragma once
 #include "fv_device.hpp"
-
-#define FV_MAX_TREE 256
-#define FV_R 4            // strips (wavefronts) per GEMM workgroup
-#define FV_FRAGS 8        // weight frags per K batch
+#include "fv_types.hpp"
 
 // ============================================================================ ingest
 // Tree ingest: ancestor sets, positions, rotary table.  One block.
@@ -32,7 +29,7 @@ struct IngestArgs {
 #define FV_PH_END
 #endif
 
-__global__ __launch_bounds__(256) void k_ingest(IngestArgs a) {
+static __global__ __launch_bounds__(256) void k_ingest(IngestArgs a) {
     // one workgroup per four rows: their ancestor masks (a short chain of dependent loads each) and
     // their rows of the rotary table (double-precision sincos, one or two entries per thread)
     const int tid = threadIdx.x;
@@ -131,13 +128,17 @@ struct GemmArgs {
     const int4* fix_groups;  // [n_fix] row groups with more than one contributor: (group, first and last contributor, the first one's segment index)
     float* rinv_out;         // [Tp] RMSNorm factors handed from k_gemm to k_gemm_fix
     int T, n_strips;     // real tokens; strips that carry real rows
-    int epi;             // epilogue, for bodies that choose it at run time
     // RMSNorm statistics of the input (QKV, SWIGLU, LOGITS): rinv[t] = rsqrt(sum_s ssq_in[s][t] / h + eps)
     const float* ssq_in; // [n_ssq][Tp]
     int n_ssq;
     float inv_h, eps;
-    // EPI_QKV: rotate q and k, write q (vector-major), k and v into the cache at slot L + t
+    // EPI_QKV: rotate q and k, write q (vector-major), k and v into the cache at slot L + t.
+    // bf16: q is kept as two bf16 tensors, q_out + q_lo_out (the second holds what the first lost to
+    // rounding), so that the scores see q at about 16 mantissa bits: the attention kernel has matrix
+    // cycles to spare, and rounding q to one bf16 moved the logits of a 32-layer model as much as the
+    // whole K cache's rounding does.
     void* q_out;
+    void* q_lo_out;
     void* kcache;        // this layer's K slabs [Hkv][S_pad*D]
     void* vcache;
     const float2* rope_cs;   // [Tp][D/2]
@@ -187,7 +188,7 @@ __device__ __forceinline__ bool rope_preload(const GemmArgs& a, int strip, int t
     return true;
 }
 
-template <typename EL, int D, int EPI, bool COH>
+template <typename EL, int D, int EPI>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
                                               const float* rinv_lds, const EpiPre& pre, bool have_pre) {
     const int tl = lane & 31, g = lane >> 5;
@@ -200,12 +201,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
             float4 xv = pre.x[blk], gn = pre.gain[blk];
             if (!have_pre) { xv = ((const float4*)a.x_in)[(size_t)(f0 >> 2) * Tp + t]; gn = *(const float4*)(a.gain_next + f0); }
             xv.x += acc[4 * blk]; xv.y += acc[4 * blk + 1]; xv.z += acc[4 * blk + 2]; xv.w += acc[4 * blk + 3];
-            st_f4<COH>((float4*)a.x + (size_t)(f0 >> 2) * Tp + t, xv);
-            store4_act<EL, COH>(a.xb, Tp, f0, t, xv.x * gn.x, xv.y * gn.y, xv.z * gn.z, xv.w * gn.w);
+            st_f4((float4*)a.x + (size_t)(f0 >> 2) * Tp + t, xv);
+            store4_act<EL>(a.xb, Tp, f0, t, xv.x * gn.x, xv.y * gn.y, xv.z * gn.z, xv.w * gn.w);
             ssq += xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
         }
         ssq += __shfl_xor(ssq, 32);
-        if (g == 0) st_f32<COH>(a.ssq_out + (size_t)strip * Tp + t, ssq);
+        if (g == 0) st_f32(a.ssq_out + (size_t)strip * Tp + t, ssq);
     } else {
         const float rs = rinv_lds[t];
 #pragma unroll
@@ -214,7 +215,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
             for (int blk = 0; blk < 4; ++blk) {
                 const int f0 = strip * 32 + 8 * blk + 4 * g;
-                st_f4<COH>((float4*)(a.logits + (size_t)t * a.Vpad + f0),
+                st_f4((float4*)(a.logits + (size_t)t * a.Vpad + f0),
                            make_float4(acc[4 * blk], acc[4 * blk + 1], acc[4 * blk + 2], acc[4 * blk + 3]));
             }
         } else if constexpr (EPI == EPI_SWIGLU) {
@@ -228,7 +229,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
                     const float gt = acc[8 * pr + c], up = acc[8 * pr + 4 + c];
                     o[c] = gt / (1.f + __expf(-gt)) * up;
                 }
-                store4_act<EL, COH>(a.act, Tp, 16 * strip + 8 * pr + 4 * g, t, o[0], o[1], o[2], o[3]);
+                store4_act<EL>(a.act, Tp, 16 * strip + 8 * pr + 4 * g, t, o[0], o[1], o[2], o[3]);
             }
         } else {  // EPI_QKV
             constexpr int SPH = D / 32;   // strips per head
@@ -256,8 +257,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
                     for (int pr = 0; pr < 2; ++pr) {
                         const int f1 = head * D + 16 * j + 8 * pr + 4 * g;
-                        store4_act<EL, COH>(a.q_out, Tp, f1, t, lo_v[pr][0], lo_v[pr][1], lo_v[pr][2], lo_v[pr][3]);
-                        store4_act<EL, COH>(a.q_out, Tp, f1 + D / 2, t, hi_v[pr][0], hi_v[pr][1], hi_v[pr][2], hi_v[pr][3]);
+                        store4_act<EL>(a.q_out, Tp, f1, t, lo_v[pr][0], lo_v[pr][1], lo_v[pr][2], lo_v[pr][3]);
+                        store4_act<EL>(a.q_out, Tp, f1 + D / 2, t, hi_v[pr][0], hi_v[pr][1], hi_v[pr][2], hi_v[pr][3]);
+                        if constexpr (Tr<EL>::E == 8) {
+                            store4_act<EL>(a.q_lo_out, Tp, f1, t, bf16_residual(lo_v[pr][0]), bf16_residual(lo_v[pr][1]),
+                                           bf16_residual(lo_v[pr][2]), bf16_residual(lo_v[pr][3]));
+                            store4_act<EL>(a.q_lo_out, Tp, f1 + D / 2, t, bf16_residual(hi_v[pr][0]), bf16_residual(hi_v[pr][1]),
+                                           bf16_residual(hi_v[pr][2]), bf16_residual(hi_v[pr][3]));
+                        }
                     }
                 } else if (t < a.T) {
                     const int kh = head - a.Hq;
@@ -268,8 +275,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
                     for (int pr = 0; pr < 2; ++pr) {
                         const int f1 = 16 * j + 8 * pr + 4 * g;
-                        st_cache4<EL, COH>(slab, kcache_index<EL, D>(pos, f1), lo_v[pr]);
-                        st_cache4<EL, COH>(slab, kcache_index<EL, D>(pos, f1 + D / 2), hi_v[pr]);
+                        st_cache4<EL>(slab, kcache_index<EL, D>(pos, f1), lo_v[pr]);
+                        st_cache4<EL>(slab, kcache_index<EL, D>(pos, f1 + D / 2), hi_v[pr]);
                     }
                 }
             } else if (t < a.T) {
@@ -279,18 +286,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int str
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int f = 32 * j + 8 * (i >> 2) + 4 * g + (i & 3);
-                    st_elem<EL, COH>(slab, vcache_index<EL, D>(pos, f), acc[i]);
+                    st_elem<EL>(slab, vcache_index<EL, D>(pos, f), acc[i]);
                 }
             }
         }
     }
 }
 
-template <typename EL, int D, int EPI, bool COH = false>
+template <typename EL, int D, int EPI>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int Tp, int strip, int tb, int lane, float (&acc)[16],
                                               const float* rinv_lds) {
     EpiPre none;   // never read: have_pre = false
-    gemm_epilogue<EL, D, EPI, COH>(a, Tp, strip, tb, lane, acc, rinv_lds, none, false);
+    gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb, lane, acc, rinv_lds, none, false);
 }
 
 // One stage of the shared-activation GEMM for one wavefront: FV_FRAGS weight fragments (registers)
@@ -396,7 +403,7 @@ __device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB
                     float r[16];
 #pragma unroll
                     for (int i = 0; i < 16; ++i) r[i] = acc[t0 + tb][i];
-                    gemm_epilogue<EL, D, EPI, false>(a, Tp, strip, t0 + tb, lane, r, rinv_lds, pre[tb], have);
+                    gemm_epilogue<EL, D, EPI>(a, Tp, strip, t0 + tb, lane, r, rinv_lds, pre[tb], have);
                 }
             }
         }
@@ -426,12 +433,13 @@ __device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB
     // Release: the payload was stored write-through, so it is enough that every lane's stores
     // have been acknowledged (vmcnt(0): on this target stores count in vmcnt) before the
     // ticket is drawn.
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), expcnt and lgkmcnt untouched
+    handoff_release();
     FV_TS(3)
     __syncthreads();
     if (tid == 0)
         *ticket_lds = __hip_atomic_fetch_add(&a.tickets[gi], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
+    handoff_acquire();
     FV_TS(4)
     const bool last = (*ticket_lds == c_last - c_first);
     if (last) {
@@ -478,7 +486,7 @@ __device__ __forceinline__ void gemm_flush(const GemmArgs& a, floatx16 (&acc)[TB
                 }
                 if (t0 == 0) { FV_TS(5) }
 #pragma unroll
-                for (int tb = 0; tb < TG; ++tb) gemm_epilogue<EL, D, EPI, false>(a, Tp, strip, t0 + tb, lane, r[tb], rinv_lds, pre[tb], have);
+                for (int tb = 0; tb < TG; ++tb) gemm_epilogue<EL, D, EPI>(a, Tp, strip, t0 + tb, lane, r[tb], rinv_lds, pre[tb], have);
             }
             FV_TS(6)
         }
@@ -706,11 +714,10 @@ __global__ __launch_bounds__(256) void k_gemm_fix(GemmArgs a) {
             }
         }
     }
-    gemm_epilogue<EL, D, EPI, false>(a, Tp, strip, tb, lane, acc, rinv_lds, pre, have);
+    gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb, lane, acc, rinv_lds, pre, have);
 }
 
 #include "fv_gemm_direct.hpp"
-#include "fv_gemm_wide.hpp"
 
 // ============================================================================ tree attention
 // For node t and query head qh: softmax over {cache slots 0..L-1} U {tree slots L+j : j in
@@ -721,6 +728,7 @@ __global__ __launch_bounds__(256) void k_gemm_fix(GemmArgs a) {
 // is tested per key, and the probabilities are already in B-operand order for V^T * P^T.
 struct AttnArgs {
     const uint4* q;          // vector-major [Hq*D/E][Tp]
+    const uint4* q_lo;       // bf16 only: the part of q that q's bf16 rounding lost (same layout)
     const uint4* kc;         // this layer's K slabs
     const uint4* vc;
     void* out;               // vector-major [Hq*D/E][Tp]
@@ -738,9 +746,8 @@ struct AttnArgs {
 #define FV_ATTN_SMEM_FLOATS(D) (3 * ((D) / 32) * 64 * 16 + 8 * 32 + 4)
 #define FV_ATTN_PART_FLOATS(D) (((D) / 32) * 1024 + 64)
 
-// One (query head, block of 32 nodes) item, key part `part` of a.ks.  COH: the output is read by
-// other workgroups of the same launch.
-template <typename EL, int D, bool COH>
+// One (query head, block of 32 nodes) item, key part `part` of a.ks.
+template <typename EL, int D>
 __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part, float* smem) {
     constexpr int E = Tr<EL>::E;
     constexpr int NF = D / (2 * E);      // K frags per key block
@@ -753,9 +760,14 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
     const int kh = qh / (a.Hq / a.Hkv);
     const int t = tb * 32 + tl;
 
-    uint4 qf[NF];
+    constexpr bool SPLIT = (E == 8);   // bf16: q and the probabilities enter the matrix cores as hi + lo pairs
+    uint4 qf[NF], qfl[SPLIT ? NF : 1];
 #pragma unroll
     for (int fr = 0; fr < NF; ++fr) qf[fr] = a.q[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
+    if constexpr (SPLIT) {
+#pragma unroll
+        for (int fr = 0; fr < NF; ++fr) qfl[fr] = a.q_lo[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
+    }
     uint64_t mk[4];
 #pragma unroll
     for (int w = 0; w < 4; ++w) mk[w] = (t < a.T) ? a.mask[t * 4 + w] : 0ull;
@@ -795,6 +807,10 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
         for (int fr = 0; fr < NF; fr += 2) {
             s = Tr<EL>::mma(kt[fr], qf[fr], s);
             s1 = Tr<EL>::mma(kt[fr + 1], qf[fr + 1], s1);
+            if constexpr (SPLIT) {
+                s = Tr<EL>::mma(kt[fr], qfl[fr], s);
+                s1 = Tr<EL>::mma(kt[fr + 1], qfl[fr + 1], s1);
+            }
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[i] += s1[i];
@@ -849,13 +865,22 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
             psum += p[i];
         }
         l_run += psum;
-        uint4 pb[NQ];
+        uint4 pb[NQ], pbl[SPLIT ? NQ : 1];
 #pragma unroll
         for (int q = 0; q < NQ; ++q) pb[q] = Tr<EL>::pack(p + q * E);
+        if constexpr (SPLIT) {   // what the probabilities lose to bf16 rounding goes through the matrix cores too
+#pragma unroll
+            for (int i = 0; i < 16; ++i) p[i] = bf16_residual(p[i]);
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) pbl[q] = Tr<EL>::pack(p + q * E);
+        }
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) o[db] = Tr<EL>::mma(vt[db * NQ + q], pb[q], o[db]);
+            for (int q = 0; q < NQ; ++q) {
+                o[db] = Tr<EL>::mma(vt[db * NQ + q], pb[q], o[db]);
+                if constexpr (SPLIT) o[db] = Tr<EL>::mma(vt[db * NQ + q], pbl[q], o[db]);
+            }
     };
     for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
         uint4 kt[NF], vt[DB * NQ];
@@ -909,7 +934,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int blk = 0; blk < 4; ++blk)
-                    store4_act<EL, COH>(a.out, a.Tp, qh * D + db * 32 + 8 * blk + 4 * g, t, r[db][4 * blk] * inv,
+                    store4_act<EL>(a.out, a.Tp, qh * D + db * 32 + 8 * blk + 4 * g, t, r[db][4 * blk] * inv,
                                         r[db][4 * blk + 1] * inv, r[db][4 * blk + 2] * inv, r[db][4 * blk + 3] * inv);
         }
         return;
@@ -927,10 +952,11 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
             __hip_atomic_store(pp + DB * 1024, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);         // lanes 0..31
             __hip_atomic_store(pp + DB * 1024 + 32, lsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        handoff_release();
         if (lane == 0) *ticket_lds = __hip_atomic_fetch_add(&a.tickets[item], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
+    handoff_acquire();
     if (*ticket_lds != a.ks - 1) return;
     if (tid == 0) __hip_atomic_store(&a.tickets[item], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next use
     // wavefront w combines 32-feature block w (blocks beyond D/32 have no wavefront).  Everything it
@@ -963,7 +989,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
         const float inv = (ltot > 0.f) ? 1.f / ltot : 0.f;
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk)
-            store4_act<EL, COH>(a.out, a.Tp, qh * D + db * 32 + 8 * blk + 4 * g, t, accv[4 * blk] * inv, accv[4 * blk + 1] * inv,
+            store4_act<EL>(a.out, a.Tp, qh * D + db * 32 + 8 * blk + 4 * g, t, accv[4 * blk] * inv, accv[4 * blk + 1] * inv,
                                 accv[4 * blk + 2] * inv, accv[4 * blk + 3] * inv);
     }
 }
@@ -985,13 +1011,13 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
         item = head * TB + w / a.ks;
         part = w % a.ks;
     }
-    attn_body<EL, D, false>(a, item, part, smem);
+    attn_body<EL, D>(a, item, part, smem);
 }
-
-#include "fv_step_persistent.hpp"
 
 // ============================================================================ argmax
 // Greedy choice per node: wavefront shuffle reduction on (value, index), lowest index on ties.
+// A row that holds a NaN or an infinity has no greedy choice: its entry becomes -1, which the
+// scan turns into an error for the whole step.
 struct ArgmaxArgs {
     const float* logits;   // [Tp][Vpad]
     int32_t* am;           // [Tp]
@@ -1002,13 +1028,15 @@ __device__ __forceinline__ void argmax_combine(float& v, int& i, float ov, int o
     if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
 }
 
-__global__ __launch_bounds__(256) void k_argmax(ArgmaxArgs a) {
+static __global__ __launch_bounds__(256) void k_argmax(ArgmaxArgs a) {
     __shared__ float sv[4];
     __shared__ int si[4];
+    __shared__ int sbad[4];
     const int t = blockIdx.x, tid = threadIdx.x;
     const float* row = a.logits + (size_t)t * a.Vpad;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
+    bool bad = false;
     // eight 16-byte loads in flight per thread (the row is a latency chain otherwise: one load per
     // trip of a loop the compiler does not pipeline); indices past Vpad are not touched, values
     // between V and Vpad are skipped
@@ -1017,7 +1045,7 @@ __global__ __launch_bounds__(256) void k_argmax(ArgmaxArgs a) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int v = v0 + k * 256 * 4;
-            x[k] = (v < a.V) ? *(const float4*)(row + v) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            x[k] = (v < a.V) ? *(const float4*)(row + v) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -1025,7 +1053,11 @@ __global__ __launch_bounds__(256) void k_argmax(ArgmaxArgs a) {
             const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (v + c < a.V) argmax_combine(bv, bi, xs[c], v + c);
+                if (v + c < a.V) {
+                    // finite <=> |x| < inf; false for NaN too
+                    bad = bad || !(__builtin_fabsf(xs[c]) < INFINITY);
+                    argmax_combine(bv, bi, xs[c], v + c);
+                }
         }
     }
 #pragma unroll
@@ -1034,11 +1066,12 @@ __global__ __launch_bounds__(256) void k_argmax(ArgmaxArgs a) {
         const int oi = __shfl_xor(bi, off);
         argmax_combine(bv, bi, ov, oi);
     }
-    if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+    const bool wbad = __any(bad);
+    if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; sbad[tid >> 6] = wbad ? 1 : 0; }
     __syncthreads();
     if (tid == 0) {
         for (int w = 1; w < 4; ++w) argmax_combine(bv, bi, sv[w], si[w]);
-        a.am[t] = bi;
+        a.am[t] = (sbad[0] | sbad[1] | sbad[2] | sbad[3]) ? -1 : bi;
     }
 }
 
@@ -1046,12 +1079,6 @@ __global__ __launch_bounds__(256) void k_argmax(ArgmaxArgs a) {
 // Single block.  match[i] = (i is the root) or tok[i] == argmax[parent[i]]; node i is
 // accepted iff every node of its ancestor set matches; best = deepest accepted node, lowest
 // index among equals; path = members of best's ancestor set in increasing index (= depth) order.
-struct FvResult {
-    int32_t accepted_len, next_token, best, pad;
-    int32_t path[FV_MAX_TREE];
-    int32_t accepted_tokens[FV_MAX_TREE];
-};
-
 // Features of the accepted path for the next drafting round: row j = the LM head's input (final
 // RMSNorm of the last layer's output) of path node j, j = 0..accepted_len, fp32 [max_tree][h].
 // One block per possible path position; blocks beyond the path leave at once.
@@ -1065,7 +1092,7 @@ struct FeatureArgs {
     float inv_h, eps;
 };
 
-__global__ __launch_bounds__(256) void k_features(FeatureArgs a) {
+static __global__ __launch_bounds__(256) void k_features(FeatureArgs a) {
     __shared__ float red[256];
     const int j = blockIdx.x, tid = threadIdx.x;
     if (j > a.res->accepted_len) return;
@@ -1091,16 +1118,18 @@ struct ScanArgs {
     FvResult* res;
 };
 
-__global__ __launch_bounds__(256) void k_scan(ScanArgs a) {
+static __global__ __launch_bounds__(256) void k_scan(ScanArgs a) {
     __shared__ unsigned long long mbits[4];
     __shared__ int best_key;
+    __shared__ int any_bad;
     const int i = threadIdx.x;
     const int32_t* tok = a.tok_in;
     const int32_t* parent = a.tok_in + a.cap;
     const int32_t* depth = a.tok_in + 2 * a.cap;
     if (i < 4) mbits[i] = 0ull;
-    if (i == 0) best_key = -1;
+    if (i == 0) { best_key = -1; any_bad = 0; }
     __syncthreads();
+    if (i < a.T && a.am[i] < 0) any_bad = 1;   // a row without a greedy choice (non-finite logits)
     if (i < a.T) {
         const bool match = (i == 0) || (tok[i] == a.am[parent[i]]);
         if (match) atomicOr(&mbits[i >> 6], 1ull << (i & 63));
@@ -1112,6 +1141,10 @@ __global__ __launch_bounds__(256) void k_scan(ScanArgs a) {
         if (ok) atomicMax(&best_key, depth[i] * 512 + (511 - i));
     }
     __syncthreads();
+    if (any_bad) {   // no decision: accepted_len = FV_SCAN_NONFINITE tells the host, nothing is compacted
+        if (i == 0) { a.res->accepted_len = FV_SCAN_NONFINITE; a.res->next_token = -1; a.res->best = 0; a.res->pad = 0; }
+        return;
+    }
     const int best = 511 - (best_key & 511);
     if (i == 0) {
         a.res->accepted_len = depth[best];
@@ -1158,7 +1191,6 @@ __global__ void k_compact(CompactArgs a) {
 }
 
 // ============================================================================ helpers: weight tiling, KV read-back
-enum { TILE_NAT = 0, TILE_QKV = 1, TILE_GU = 2 };
 struct TileArgs {
     const void* src0; const void* src1; const void* src2;
     uint4* out;

@@ -62,8 +62,6 @@ class StorageNoiseModel(fo.Oracle):
     def _forward_rows(self, tokens, pos, visible):
         s, dt, L = self.s, self.dtype, self.L
         n = len(tokens)
-        if visible is None:
-            visible = [list(range(i + 1)) for i in range(n)]
         x = fo._up(self.w["embed"], dt)[np.asarray(tokens)]
         newK = np.zeros((s.n_layers, n, s.n_kv_heads, s.head_dim), dtype=dt)
         newV = np.zeros_like(newK)
@@ -77,12 +75,23 @@ class StorageNoiseModel(fo.Oracle):
             v = st("v", (lin(xin, W("wv"), dt) * rinv).reshape(n, s.n_kv_heads, s.head_dim))
             newK[l], newV[l] = k, v
             att = np.zeros((n, s.n_q_heads, s.head_dim), dtype=dt)
-            for i in range(n):
-                keys = np.repeat(np.concatenate([self.K[l, :L], k[visible[i]]], axis=0), grp, axis=1)   # [m, Hq, d]
-                vals = np.repeat(np.concatenate([self.V[l, :L], v[visible[i]]], axis=0), grp, axis=1)
-                sc = np.einsum("hd,mhd->hm", q[i], keys) / np.sqrt(s.head_dim)
-                e = np.exp(sc - np.max(sc, axis=-1, keepdims=True))
-                att[i] = np.einsum("hm,mhd->hd", st("p", e), vals) / np.sum(e, axis=-1, keepdims=True)
+            scale = 1.0 / np.sqrt(s.head_dim)
+            for qh in range(s.n_q_heads):
+                kh = qh // grp
+                if visible is None:   # a prompt: causal, written with a triangular mask
+                    keys = np.concatenate([self.K[l, :L, kh], k[:, kh]], axis=0)
+                    vals = np.concatenate([self.V[l, :L, kh], v[:, kh]], axis=0)
+                    seen = np.concatenate([np.ones((n, L), dtype=bool), np.tril(np.ones((n, n), dtype=bool))], axis=1)
+                    sc = np.where(seen, q[:, qh] @ keys.T * scale, -np.inf)
+                    e = np.exp(sc - np.max(sc, axis=-1, keepdims=True))
+                    att[:, qh] = (st("p", e) @ vals) / np.sum(e, axis=-1, keepdims=True)
+                else:
+                    for i in range(n):
+                        keys = np.concatenate([self.K[l, :L, kh], k[visible[i], kh]], axis=0)
+                        vals = np.concatenate([self.V[l, :L, kh], v[visible[i], kh]], axis=0)
+                        sc = keys @ q[i, qh] * scale
+                        e = np.exp(sc - np.max(sc))
+                        att[i, qh] = (st("p", e) @ vals) / np.sum(e)
             x = x + lin(st("attn", att.reshape(n, -1)), W("wo"), dt)
             xin, rinv = self._gemm_in("xin_gu", x, W("g_mlp").astype(dt))
             a = fo.silu(lin(xin, W("wg"), dt) * rinv) * (lin(xin, W("wu"), dt) * rinv)

@@ -13,17 +13,9 @@ pytestmark = pytest.mark.gpu
 
 
 def say(*a):
-    """Progress line: to stdout, and (output capture or not) appended to a file that a watcher of a
-    long run can see."""
+    """Progress line on stdout (run pytest with -s or -v to see it; nothing is written to disk)."""
     print("[case]", *a, flush=True)
     sys.stdout.flush()
-    try:
-        import os
-        os.makedirs("gpurun_out", exist_ok=True)
-        with open(os.path.join("gpurun_out", "test_progress.log"), "a") as f:
-            f.write(" ".join(str(x) for x in a) + "\n")
-    except OSError:
-        pass
 
 
 @pytest.fixture(scope="module")
@@ -204,7 +196,7 @@ def test_multi_chunk_prefill_and_multi_step_decode(fvmod, name):
             say("step", step, "near-tie on the greedy path: stop here")
             break
         a, acc, nxt = g.verify_tree(tokens, parent, depth)
-        case = dict(res=res, parent=parent)
+        case = dict(res=res, parent=parent, tokens=tokens, depth=depth, hidden=o.last_hidden.copy())
         e = H.check_step(g, case, (a, acc, nxt), tol)
         say("step", step, "err", e, "accepted", a)
         emitted_g += list(acc) + [nxt]
@@ -284,45 +276,59 @@ def test_rejected_calls_change_nothing(fvmod):
     g.close()
 
 
-@pytest.mark.parametrize("name,gemm", [("tiny", "direct"), ("small-gqa", "direct"), ("small-gqa-f32", "paired")])
-def test_persistent_kernel_and_per_gemm_path_agree(fvmod, name, gemm, monkeypatch):
-    """Steps of up to 64 nodes take one launch per GEMM by default; FV_PERSISTENT=1 runs all layers
-    in one persistent kernel, whose GEMM phases are the direct-operand kernel's body (paired form if
-    every layer matrix takes it, as on small-gqa-f32; else one strip per wavefront).  Both must match
-    the oracle, and -- with the same GEMM form on the per-launch side -- each other bit for bit (same
-    split, same summation order)."""
-    s, w = SHAPES[name], weights_of(name)
-    tol = H.tol_for(s)
-    say("persistent-vs-launches", name, gemm)
-    case = H.planted_case(s, w, 70, 48, [6, 3, 2, 2, 1, 1], 3, seed=2)
-    outs = []
-    monkeypatch.setenv("FV_GEMM", gemm)
-    for flag in ("1", "0"):
-        monkeypatch.setenv("FV_PERSISTENT", flag)
-        g = make_gpu(fvmod, s, w, max_seq=160, max_tree=64)
-        assert g.prefill(case["prefix"]) == case["root"]
-        got = g.verify_tree(case["tokens"], case["parent"], case["depth"])
-        e = H.check_step(g, case, got, tol)
-        say("FV_PERSISTENT=" + flag, "err", e, "step ms", g.last_step_ms())
-        outs.append(g.logits(48).copy())
-        H.check_cache(g, case["oracle"], s, 70 + got[0] + 1, tol)
-        g.close()
-    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+def test_non_finite_logits_are_an_error_not_a_choice(fvmod):
+    """A NaN among the logits leaves no greedy choice: the oracle raises, the library returns
+    FV_E_NONFINITE and leaves the committed length and pending root as they were."""
+    from fv_inputs.trees import fill_tokens
+    s = SHAPES["tiny-bf16"]
+    say("non-finite")
+    prefix = fi.gen_prefix(0, 20, s.vocab)
+    # (a) prompt: a row of NaNs in the LM head makes token 7's logit NaN in every row
+    w = dict(weights_of("tiny-bf16"))
+    bad = w["lm_head"].copy()
+    bad[7, :] = 0x7FC0
+    w["lm_head"] = bad
+    with pytest.raises(FloatingPointError):
+        fo.Oracle(s, w, max_seq=64).prefill(prefix)
+    g = make_gpu(fvmod, s, w, max_seq=64, max_tree=16)
+    with pytest.raises(fvmod.FvError) as ei:
+        g.prefill(prefix)
+    assert ei.value.status == -10
+    g.close()
+    # (b) verification: the embedding of a token that only one tree node carries is NaN, so that
+    # node's logits are NaN and the step has no decision
+    w = dict(weights_of("tiny-bf16"))
+    poison = next(t for t in range(s.vocab) if t not in set(int(x) for x in prefix))
+    emb = w["embed"].copy()
+    emb[poison, :] = 0x7FC0
+    w["embed"] = emb
+    o = fo.Oracle(s, w, max_seq=64)
+    root = o.prefill(prefix)
+    assert root != poison
+    parent, depth, _ = fi.gen_tree(1, 9, [3, 2, 1])
+    tok = fill_tokens(1, parent, s.vocab, root)
+    tok[5] = poison
+    with pytest.raises(FloatingPointError):
+        o.verify_tree(tok, parent, depth)
+    g = make_gpu(fvmod, s, w, max_seq=64, max_tree=16)
+    assert g.prefill(prefix) == root
+    with pytest.raises(fvmod.FvError) as ei:
+        g.verify_tree(tok, parent, depth)
+    assert ei.value.status == -10 and g.state() == (20, root)
+    g.close()
 
 
-@pytest.mark.parametrize("kind", ["direct", "paired", "wide", "shared"])
+@pytest.mark.parametrize("kind", ["direct", "paired", "shared"])
 @pytest.mark.parametrize("name", ["tiny", "small-gqa", "small-gqa-f32"])
 def test_alternative_gemm_kernels_match_the_oracle(fvmod, name, kind, monkeypatch):
     """Up to 64 tokens the GEMMs default to the paired form of the direct-operand kernel wherever the
     K range is long enough for it (all matrices of small-gqa-f32, O and down of small-gqa, down of
-    tiny) and to the one-strip form elsewhere; FV_GEMM forces the one-strip form ("direct"), the
-    four-strips-per-wavefront kernel ("wide") or the LDS-shared-activation kernel ("shared").  Same bar
-    against the oracle for each."""
+    tiny) and to the one-strip form elsewhere; FV_GEMM forces the one-strip form ("direct") or the
+    LDS-shared-activation kernel ("shared").  Same bar against the oracle for each."""
     s, w = SHAPES[name], weights_of(name)
     tol = H.tol_for(s)
     say("gemm-kind", kind, name)
     monkeypatch.setenv("FV_GEMM", kind)
-    monkeypatch.setenv("FV_PERSISTENT", "0")
     for n_nodes in (48, 17):
         case = H.planted_case(s, w, 70, n_nodes, [6, 3, 2, 2, 1, 1], 3, seed=4)
         g = make_gpu(fvmod, s, w, max_seq=160, max_tree=64)
@@ -369,129 +375,171 @@ def test_partial_tile_reduction_modes_above_64_rows(fvmod, name, mode, monkeypat
 _REDUCTION_LOGITS = {}
 
 
-def _full_size_case(s, w, L, n_nodes, branching, plant, seed, deep=False):
-    """One seeded instance at benchmark size, no search for comfortable margins (the oracle pass is
-    too slow to repeat): prefix, tree with the oracle's greedy tokens planted, oracle results.
-    deep=True (all layers): fp32 working precision for speed, and the logits of the same tree from
-    the oracle with the bf16 storage formats written in come along as `storage_logits`."""
+def _oracle_weights(w):
+    """The same weights widened to fp32 once (exact), so that the oracle does not widen a matrix again
+    at every use: matters at benchmark widths."""
+    return {k: (fi.f32_from_bf16_bits(v) if v.dtype == np.uint16 else v) for k, v in w.items()}
+
+
+def _wide_case(s, w, L, n_nodes, branching, plant, seed, tol, max_last_tokens=400):
+    """One instance at a benchmark width whose deciding rows have clear margins, found cheaply: the
+    oracle's pass over the first L-1 prompt tokens (the slow part; fp32 working precision bounds it)
+    runs once, then candidates for the LAST prompt token are tried with single-row steps until the
+    rows that decide the root and the planted greedy tokens all have a top-2 gap above
+    2*tol*max|row| (so that a device within tol of the oracle must take the same decisions).
+    max_last_tokens=1 takes the first candidate whatever its margins."""
     from fv_inputs.trees import fill_tokens
-    kw = dict(dtype=np.float32) if deep else {}
     prefix = fi.gen_prefix(seed, L, s.vocab)
-    o = fo.Oracle(s, w, max_seq=L + n_nodes + 8, **kw)
-    root = o.prefill(prefix)
-    say("oracle prefill done")
-    prefill_last = o.last_logits[-1].copy()
-    greedy, tk = [], root
+    o = fo.Oracle(s, _oracle_weights(w), max_seq=L + n_nodes + 8, dtype=np.float32)
+    o.prefill(prefix[:L - 1])
+    say("oracle prompt pass done")
     p1, d1 = fi.chain_tree(1)
-    for _ in range(plant):
-        tk = o.verify_tree(np.array([tk], dtype=np.int32), p1, d1)["next_token"]
-        greedy.append(tk)
-        say("oracle greedy token", len(greedy))
-    o.rollback(L, root)
-    parent, depth, planted = fi.gen_tree(seed, n_nodes, branching, plant)
-    tokens = fill_tokens(seed, parent, s.vocab, root, planted, greedy)
-    res = o.verify_tree(tokens, parent, depth)
-    say("oracle verify done")
-    storage_logits = None
-    if deep:
-        ob = fo.Oracle(s, w, max_seq=L + n_nodes + 8, dtype=np.float32, storage="bf16")
-        ob.prefill(prefix)
-        say("storage-model oracle prefill done")
-        ob.rollback(L, root)
-        storage_logits = ob.verify_tree(tokens, parent, depth)["logits"]
-        say("storage-model oracle verify done")
+    rng = np.random.Generator(np.random.Philox(key=[seed, 7100]))
+    for attempt in range(max_last_tokens):
+        cand = int(prefix[L - 1]) if attempt == 0 else int(rng.integers(0, s.vocab))
+        o.rollback(L - 1, cand)
+        chain, tk, clear, rows = [], cand, True, []
+        for j in range(plant + 2):   # rows of: the last prompt token, the root, the planted nodes
+            r = o.verify_tree(np.array([tk], dtype=np.int32), p1, d1)
+            row = r["logits"][0]
+            rows.append(row.copy())
+            clear = clear and fo.top2_margin(row) > 2 * tol * np.max(np.abs(row))
+            if not clear and max_last_tokens > 1:
+                break
+            tk = r["next_token"]
+            chain.append(tk)
+        if clear or max_last_tokens == 1:
+            break
+    else:
+        raise RuntimeError("no last prompt token with clear margins found")
+    prefix = np.concatenate([prefix[:L - 1], np.array([cand], dtype=np.int32)])
+    root, greedy = chain[0], chain[1:plant + 1]
+    say("last prompt token candidates tried:", attempt + 1)
+    for t in range(12):
+        o.rollback(L, root)
+        sd = seed + 1000 * t
+        parent, depth, planted = fi.gen_tree(sd, n_nodes, branching, plant)
+        tokens = fill_tokens(sd, parent, s.vocab, root, planted, greedy)
+        res = o.verify_tree(tokens, parent, depth)
+        clear = H.decision_margins_ok(res, tokens, parent, tol)
+        if clear or max_last_tokens == 1:
+            break
+    say("oracle verify done; tree draws:", t + 1, "deciding margins clear:", clear)
     return dict(prefix=prefix, root=root, parent=parent, depth=depth, tokens=tokens, oracle=o, res=res,
-                prefill_last=prefill_last, storage_logits=storage_logits)
+                prefill_last=rows[0], hidden=o.last_hidden.copy(), clear=clear, plant=plant)
 
 
-def _check_full_size(fvmod, s, w, case, L, T):
-    """Tolerance.  Up to 4 layers: the usual one.  Deeper: every tensor a bf16 configuration stores in
-    bf16 (about nine per layer) carries independent rounding noise of ~2^-9 relative, which adds in
-    quadrature over the layers and re-randomises within a few stages (an fp32-sized difference upstream
-    flips enough roundings to become a bf16-sized one), so no implementation with these storage formats
-    can sit closer to the exact result than that noise.  The bound is therefore the shallow tolerance
-    widened by sqrt(NL / 4), AND the device must not be further from the exact logits than 1.3x what the
-    oracle itself moves by when the same storage formats are written into it."""
-    tol = H.tol_for(s) * max(1.0, float(np.sqrt(s.n_layers / 4.0)))
-    g = make_gpu(fvmod, s, w, max_seq=L + 256 + 8, max_tree=256)   # the configuration bench.py times
+def _run_wide(fvmod, s, w, case, L, T, tol, max_tree=256):
+    """Device step on a _wide_case instance, in the launch configuration bench.py times (max_tree 256)."""
+    g = make_gpu(fvmod, s, w, max_seq=L + max_tree + 8, max_tree=max_tree)
     groot = g.prefill(case["prefix"])
-    res = case["res"]
     pl = case["prefill_last"]
     if fo.top2_margin(pl) > tol * np.max(np.abs(pl)):
         assert groot == case["root"]
+    ec = H.check_cache(g, case["oracle"], s, 0 + L, tol) if s.n_layers <= 4 else None
     if groot != case["root"]:
         g.rollback(L, case["root"])
     got = g.verify_tree(case["tokens"], case["parent"], case["depth"])
-    assert np.array_equal(g.tree_mask(T), res["mask"])
-    logits = g.logits(T)
-    assert np.all(np.isfinite(logits))
-    ref = res["logits"].astype(np.float64)
-    err = H.row_rel_err(logits.astype(np.float64), ref)
-    say("full-size logits err: max", err.max(), "median", float(np.median(err)), "bound", tol)
-    assert err.max() <= tol
-    if case["storage_logits"] is not None:
-        noise = H.row_rel_err(case["storage_logits"].astype(np.float64), ref)
-        say("storage-model oracle's own distance from the exact logits: max", noise.max(), "median", float(np.median(noise)))
-        assert err.max() <= 1.3 * noise.max() and np.median(err) <= 1.3 * np.median(noise)
-    am = g.argmax(T)
-    clear = 0
-    for i in range(T):
-        row = res["logits"][i]
-        if fo.top2_margin(row) > tol * np.max(np.abs(row)):
-            assert am[i] == res["argmax"][i]
-            clear += 1
-        assert am[i] == int(np.argmax(logits[i]))
-    say("argmax checked on", clear, "of", T, "nodes with a clear oracle margin")
-    # With every row within e of the oracle, the acceptance decisions must agree wherever the deciding
-    # rows' top-2 gaps exceed 2e; e is the error just measured (<= tol), not the tolerance itself.
-    e = float(err.max()) * 1.01
-    a, acc, nxt = got
-    if H.decision_margins_ok(res, case["tokens"], case["parent"], e):
-        assert a == res["accepted_len"] and list(acc) == list(res["accepted_tokens"]) and nxt == res["next_token"]
-        src, dst = g.kv_moves()
-        assert list(src) == list(res["src_slot"]) and list(dst) == list(res["dst_slot"])
-        assert g.state() == (case["oracle"].L, case["oracle"].pending)
-        ec = H.check_cache(g, case["oracle"], s, L + a + 1, tol)
-        say("decisions equal the oracle's; accepted", a, "cache err", ec)
-    else:
-        # a near-tie on a deciding row: only what is unique can be demanded -- the device's path must be
-        # the greedy walk of its OWN argmax over the tree
-        node, walked = 0, []
-        while True:
-            nxt_node = [j for j in range(1, T) if int(case["parent"][j]) == node and int(case["tokens"][j]) == int(am[node])]
-            if not nxt_node:
-                break
-            node = nxt_node[0]
-            walked.append(int(case["tokens"][node]))
-        assert list(acc) == walked and nxt == int(am[node])
-        src, dst = g.kv_moves()
-        assert list(dst) == list(range(L, L + a + 1)) and len(src) == a + 1 and src[0] == 0
-        say("near-tie on a deciding row: device path checked against its own argmax; accepted", a)
-    g.close()
-    return float(err.max())
+    return g, got, ec
 
 
-def test_benchmark_shape_two_layers_elementwise(fvmod):
-    """The 7B shape of the benchmark (hidden 4096, 32 heads x 128, FFN 11008, vocab 32000, prefix 512,
-    64-node tree) truncated to two layers, so that the oracle finishes in seconds: every logit of every
-    node, the caches, and the decisions, in the launch configuration bench.py times."""
-    s = fi.SHAPES["7b"].with_layers(2)
+@pytest.mark.parametrize("name,L,T,br,plant", [
+    ("7b", 512, 64, [8, 4, 2, 2, 1, 1], 3),        # the benchmark's headline shape
+    ("7b", 2048, 128, "random", 2),                # tree-size sweep: the LDS-shared GEMM + separate reduction launch
+    ("7b", 2048, 256, "random", 2),
+    ("13b", 1024, 64, [8, 4, 2, 2, 1, 1], 2),      # hidden 5120, 40 heads, FFN 13824
+    ("70b", 2048, 32, [4, 2, 2, 1, 1], 2),         # hidden 8192, 64 query / 8 KV heads, FFN 28672
+])
+def test_benchmark_widths_two_layers_elementwise(fvmod, name, L, T, br, plant):
+    """Every shape of the benchmark list truncated to two layers, so that the oracle finishes in
+    seconds to a minute: every logit of every node within 2e-2, prompt cache, compacted cache, and
+    the integer outputs bit-exact against the oracle (the tree is re-drawn until the deciding
+    margins are clear of the tolerance)."""
+    s = fi.SHAPES[name].with_layers(2)
+    tol = H.tol_for(s)
+    say("width", name, "x 2 layers, prefix", L, "nodes", T)
     w = fi.gen_weights(s, seed=0)
-    say("7b x 2 layers")
-    case = _full_size_case(s, w, 512, 64, [8, 4, 2, 2, 1, 1], 3, seed=0)
-    _check_full_size(fvmod, s, w, case, 512, 64)
+    branching = fi.random_branching(T, T) if br == "random" else br
+    case = _wide_case(s, w, L, T, branching, plant, seed=T, tol=tol)
+    assert case["clear"], "no tree with clear deciding margins in 12 draws"
+    g, got, ec = _run_wide(fvmod, s, w, case, L, T, tol)
+    e = H.check_step(g, case, got, tol, L=L)
+    say("logits err", e, "(bar 2e-2); prompt cache err", ec, "; accepted", got[0])
+    assert got[0] == plant
+    H.check_cache(g, case["oracle"], s, L + plant + 1, tol)
+    g.close()
+
+
+_DEEP = {}
 
 
 @pytest.mark.timeout(1500)
 def test_benchmark_configuration_all_layers(fvmod):
-    """The benchmark's own configuration, all 32 layers (about two minutes of CPU for the oracles):
-    logits within the depth-scaled bound and no further from the exact ones than the bf16 storage formats
-    alone put the oracle; decisions bit-exact where the deciding gaps are clear of the measured error."""
+    """The benchmark's own configuration, all 32 layers (minutes of CPU for the oracle and the noise model).
+
+    Integer outputs: bit-exact, unconditionally, against the oracle's acceptance rule applied to the
+    device's argmax; and equal to the oracle's own decisions where the oracle's deciding margins are
+    clear of the error measured on this instance.  Compacted K/V of the path taken: against the
+    oracle's per-node K/V.  Logits: the 2e-2 bar of the shallow shapes is NOT met at this depth (see
+    test_all_layers_logits_against_the_2e-2_bar, which reports it); what is asserted here is that the
+    device is no further from the exact logits than 1.1x what the bf16 formats that the configuration
+    fixes (GEMM inputs and K/V cache) put between the noise model and the exact logits, and the
+    depth-scaled bound 2e-2*sqrt(NL/4)."""
+    from tests import bf16_noise_model as nm
     s = fi.SHAPES["7b"]
+    L, T = 512, 64
     w = fi.gen_weights(s, seed=0)
-    say("7b, 32 layers: oracle prefill + verify on the host ...")
-    case = _full_size_case(s, w, 512, 64, [8, 4, 2, 2, 1, 1], 3, seed=0, deep=True)
-    _check_full_size(fvmod, s, w, case, 512, 64)
+    say("7b, 32 layers: oracle prompt pass + verify on the host ...")
+    tol = H.tol_for(s)
+    case = _wide_case(s, w, L, T, [8, 4, 2, 2, 1, 1], 3, seed=0, tol=tol, max_last_tokens=1)
+    g, got, _ = _run_wide(fvmod, s, w, case, L, T, tol)
+    res = case["res"]
+    assert np.array_equal(g.tree_mask(T), res["mask"])
+    logits = g.logits(T)
+    ref = res["logits"].astype(np.float64)
+    err = H.row_rel_err(logits.astype(np.float64), ref)
+    _DEEP["err"] = err
+    bound = tol * float(np.sqrt(s.n_layers / 4.0))
+    say("all-layers logits err: max", err.max(), "median", float(np.median(err)), "-- the 2e-2 bar is",
+        "met" if err.max() <= tol else "NOT met", "; depth-scaled bound", bound)
+    d = H.check_decisions(g, case["tokens"], case["parent"], case["depth"], L, got)
+    ek = H.check_path_cache(g, s, L, d["path"], res["tree_k"], res["tree_v"], bound)
+    say("decisions = acceptance rule of the device argmax; accepted", d["accepted_len"], "; compacted K/V err", ek)
+    feat = g.features(d["accepted_len"] + 1).astype(np.float64)
+    assert H.row_rel_err(feat, case["hidden"][d["path"]].astype(np.float64)).max() <= bound
+    am = g.argmax(T)
+    clear = [i for i in range(T) if fo.top2_margin(res["logits"][i]) > 2 * err[i] * np.max(np.abs(res["logits"][i]))]
+    for i in clear:   # a row's argmax cannot move if its top-2 gap exceeds twice that row's own error
+        assert am[i] == res["argmax"][i], f"argmax of node {i}"
+    say("argmax equals the oracle's on the", len(clear), "of", T, "rows whose gap exceeds twice their measured error")
+    if H.decision_margins_ok(res, case["tokens"], case["parent"], float(err.max()) * 1.01):
+        assert d["accepted_len"] == res["accepted_len"] and list(d["path"]) == list(res["path"]) and d["next_token"] == res["next_token"]
+        say("decisions also equal the oracle's own")
+    else:
+        say("a deciding row of the ORACLE is a near-tie at this depth: oracle decisions not demanded")
+    g.close()
+    assert err.max() <= bound
+    # the formats the configuration fixes, alone, in the noise model
+    fl = nm.StorageNoiseModel(s, _oracle_weights(w), max_seq=L + T + 8, dtype=np.float32, rounded=nm.GEMM_INPUTS + nm.KV_CACHE)
+    fl.prefill(case["prefix"])
+    fl.rollback(L, case["root"])
+    floor = H.row_rel_err(fl.tree_logits(case["tokens"], case["parent"], case["depth"])[0].astype(np.float64), ref)
+    say("noise model, bf16 GEMM inputs + K/V cache only: max", floor.max(), "median", float(np.median(floor)))
+    _DEEP["floor"] = floor
+    assert np.median(err) <= 1.1 * np.median(floor) and err.max() <= 1.25 * floor.max()
+
+
+def test_all_layers_logits_against_the_2e_2_bar():
+    """The stated bar, 2e-2 of the row maximum, on the 32-layer benchmark configuration.  Recorded as
+    an expected failure while the measured error exceeds it: with bf16 GEMM inputs and a bf16 K/V
+    cache, which the configuration fixes, the rounding noise of those formats alone is above the bar
+    at this depth (the previous test measures both figures)."""
+    if "err" not in _DEEP:
+        pytest.skip("needs the all-layers test of this module to have run")
+    e = float(_DEEP["err"].max())
+    if e > 2e-2:
+        pytest.xfail(f"2e-2 bar NOT met at 32 layers: measured {e:.3e}"
+                     + (f"; bf16 GEMM inputs + K/V cache alone give {float(_DEEP['floor'].max()):.3e}" if "floor" in _DEEP else ""))
 
 
 @pytest.mark.parametrize("name", ["small-gqa-f32", "small-gqa"])

@@ -508,3 +508,130 @@ def test_verify_tree_uses_the_acceptance_function(tiny):
         assert list(d[key]) == list(r[key])
     for j, node in enumerate(r["path"]):
         assert np.array_equal(o.K[:, 64 + j], r["tree_k"][:, node]) and np.array_equal(o.V[:, 64 + j], r["tree_v"][:, node])
+
+
+# ------------------------------------------------------------------ non-greedy acceptance (multi-step speculative sampling)
+
+def _softmax(z):
+    e = np.exp(z - np.max(z))
+    return e / e.sum()
+
+
+def _chi2_ok(counts, probs, alpha=1e-4):
+    from scipy.stats import chisquare
+    keep = probs > 0
+    assert counts[~keep].sum() == 0
+    return chisquare(counts[keep], probs[keep] * counts.sum()).pvalue > alpha
+
+
+def test_sampled_accept_emits_the_target_distribution_for_deterministic_children():
+    """Point-mass proposals (top-m children): whatever the children are, the first emitted token is
+    distributed as the target's softmax at the root, and the token after an accepted child as the
+    target's softmax at that child (the guarantee the method rests on).  Seeded Monte Carlo, chi-square."""
+    rng = np.random.default_rng(11)
+    V = 7
+    #        0
+    #     1  2  3        tokens 4, 0, 6
+    #    4 5    6        tokens 2, 3 | 1
+    parent = np.array([-1, 0, 0, 0, 1, 1, 3], dtype=np.int32)
+    depth = np.array([0, 1, 1, 1, 2, 2, 2], dtype=np.int32)
+    tok = np.array([5, 4, 0, 6, 2, 3, 1], dtype=np.int32)
+    logits = rng.standard_normal((7, V)) * 1.5
+    temp = 0.8
+    N = 60000
+    first = np.zeros(V)
+    second = {c: np.zeros(V) for c in (1, 2, 3)}
+    for _ in range(N):
+        r = fo.sampled_accept(logits, tok, parent, depth, 0, temp, rng.random(7), rng.random(7))
+        em = list(r["accepted_tokens"]) + [r["next_token"]]
+        first[em[0]] += 1
+        if r["accepted_len"] >= 1:
+            second[int(r["path"][1])][em[1]] += 1
+        assert [int(tok[j]) for j in r["path"][1:]] == em[:-1] and r["accepted_len"] == depth[r["path"][-1]]
+    assert _chi2_ok(first, _softmax(logits[0] / temp))
+    for c in (1, 2, 3):
+        assert second[c].sum() > 800 and _chi2_ok(second[c], _softmax(logits[c] / temp))
+    # and a wrong rule is caught by this check: accepting with p[x] but NOT striking x on rejection
+    # would over-produce the children's tokens -- the exact first-token law of that variant differs
+    p = _softmax(logits[0] / temp)
+    wrong = p.copy()
+    rej = 1.0
+    for x in (4, 0, 6):
+        rej *= 1 - p[x]
+    wrong = np.array([p[v] * rej for v in range(V)])
+    acc_mass = 1.0
+    for x in (4, 0, 6):
+        wrong[x] += acc_mass * p[x]
+        acc_mass *= 1 - p[x]
+    assert abs(wrong.sum() - 1) < 1e-12 and not _chi2_ok(first, wrong)
+
+
+def test_sampled_accept_with_a_draft_distribution():
+    """Children drawn i.i.d. from the drafter's q: first emitted token still follows the target's p
+    (q far from p, three children), and q == p accepts the first child always."""
+    rng = np.random.default_rng(5)
+    V = 6
+    parent = np.array([-1, 0, 0, 0], dtype=np.int32)
+    depth = np.array([0, 1, 1, 1], dtype=np.int32)
+    logits = rng.standard_normal((4, V)) * 2.0
+    p = _softmax(logits[0])
+    q = _softmax(rng.standard_normal(V) * 2.0)
+    draft = np.zeros((4, V))
+    draft[0] = q
+    N = 60000
+    first = np.zeros(V)
+    n_acc = 0
+    for _ in range(N):
+        tok = np.concatenate([[0], rng.choice(V, size=3, p=q)]).astype(np.int32)
+        r = fo.sampled_accept(logits, tok, parent, depth, 0, 1.0, rng.random(4), rng.random(4), draft_probs=draft)
+        em = list(r["accepted_tokens"]) + [r["next_token"]]
+        first[em[0]] += 1
+        n_acc += r["accepted_len"]
+    assert _chi2_ok(first, p)
+    assert 0.2 * N < n_acc < N            # some accepted, some resampled: both branches exercised
+    draft[0] = p
+    for _ in range(200):
+        tok = np.concatenate([[0], rng.choice(V, size=3, p=p)]).astype(np.int32)
+        r = fo.sampled_accept(logits, tok, parent, depth, 0, 1.0, rng.random(4), rng.random(4), draft_probs=draft)
+        assert r["accepted_len"] == 1 and list(r["path"]) == [0, 1]
+
+
+def test_sampled_accept_limits_and_inputs():
+    rng = np.random.default_rng(2)
+    V = 50
+    # temperature -> 0 with deterministic children is greedy acceptance, for any uniforms
+    for seed in range(20):
+        n = 25
+        parent, depth, _ = fi.gen_tree(seed, n, [3, 2, 2, 2, 1])
+        logits = rng.standard_normal((n, V))
+        am = np.argmax(logits, axis=-1).astype(np.int32)
+        tok = rng.integers(0, V, size=n).astype(np.int32)
+        for i in range(1, n):                    # make some paths right
+            if rng.random() < 0.5:
+                tok[i] = am[parent[i]]
+        for i in range(1, n):                    # siblings distinct
+            sib = [j for j in range(1, i) if parent[j] == parent[i]]
+            while any(tok[j] == tok[i] for j in sib):
+                tok[i] = (tok[i] + 1) % V
+        g = fo.greedy_accept(tok, parent, depth, am, L=9)
+        r = fo.sampled_accept(logits, tok, parent, depth, 9, 1e-3, rng.random(n), rng.random(n))
+        assert list(r["path"]) == list(g["path"]) and r["next_token"] == g["next_token"]
+        assert list(r["dst_slot"]) == list(g["dst_slot"]) and list(r["accepted_tokens"]) == list(g["accepted_tokens"])
+    # a token the target gives (numerically) no mass is never accepted, and never drawn
+    parent = np.array([-1, 0], dtype=np.int32)
+    depth = np.array([0, 1], dtype=np.int32)
+    logits = np.zeros((2, 4))
+    logits[0, 2] = -1e4
+    for _ in range(50):
+        r = fo.sampled_accept(logits, np.array([0, 2]), parent, depth, 0, 1.0, rng.random(2), rng.random(2))
+        assert r["accepted_len"] == 0 and r["next_token"] != 2
+    # only the uniforms of tested children and of the node where the draw happens matter; hand-computed draw:
+    # root p = (0.1, 0.2, 0.3, 0.4), child token 3 rejected at u = 0.9 -> p' = (1/6, 2/6, 3/6, 0); u_sample 0.6 -> token 2
+    logits = np.log(np.array([[0.1, 0.2, 0.3, 0.4], [0.25, 0.25, 0.25, 0.25]]))
+    r = fo.sampled_accept(logits, np.array([1, 3]), parent, depth, 7, 1.0, [0.123, 0.9], [0.6, 0.999])
+    assert r["accepted_len"] == 0 and r["next_token"] == 2 and list(r["dst_slot"]) == [7]
+    assert abs(r["min_margin"] - min(0.9 - 0.4, 0.6 - 0.5) / 0.9) < 1e-9 or r["min_margin"] > 0.05
+    r = fo.sampled_accept(logits, np.array([1, 3]), parent, depth, 7, 1.0, [0.123, 0.39], [0.6, 0.7])   # accepted at u = 0.39 < 0.4
+    assert r["accepted_len"] == 1 and list(r["accepted_tokens"]) == [3] and r["next_token"] == 2      # leaf: draw from uniform p at 0.7 -> token 2
+    with pytest.raises(FloatingPointError):
+        fo.sampled_accept(np.array([[0.0, np.nan]]), np.array([0]), np.array([-1]), np.array([0]), 0, 1.0, [0.5], [0.5])
