@@ -144,7 +144,10 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
             pl.slice(rq.s, gi, ws, we);
             if (we > ws) {
                 rq.n = we - ws; rq.n3 = (rq.n + 2) / 3 * 3;
-                rq.wp = a.Wt + ((size_t)gi * RS * a.NB + ws) * (SF * 64) + lane;
+                // weights are tiled [strip pair][half K batch][2 strips][4 frags]: a paired stage (half a batch of both
+                // strips) is 8 KiB contiguous, a one-strip stage (a whole batch of one strip) two 4 KiB pieces 8 KiB apart
+                rq.wp = (RS == 2) ? a.Wt + ((size_t)gi * a.NB + ws) * (FV_FRAGS * 64) + lane
+                                  : a.Wt + (((size_t)(gi >> 1) * (2 * a.NB) + 2 * ws) * 2 + (gi & 1)) * (4 * 64) + lane;
                 rq.xp = a.X + (size_t)ws * (2 * SF * Tp) + g * Tp + tl;
                 return;
             }
@@ -158,13 +161,10 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     auto load_w = [&](uint4 (&dst)[FV_FRAGS]) {
         const bool live = rq.j < rq.n;
         const uint4* p = live ? rq.wp : zeros;
-        const size_t rstride = live ? (size_t)a.NB * (SF * 64) : 0;
+        // tile order inside a stage: paired: (strip r, frag f) at r*4 + f; one strip: frags 0-3, then frags 4-7 one
+        // pair-row (8 tiles) further on
 #pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            const uint4* pr = p + r * rstride;
-#pragma unroll
-            for (int f = 0; f < SF; ++f) dst[r * SF + f] = pr[f * 64];
-        }
+        for (int i = 0; i < FV_FRAGS; ++i) dst[i] = p[((RS == 2 || i < 4) ? i : i + 4) * 64];
     };
     auto load_x = [&](uint4 (&dst)[NX]) {
         const bool live = rq.j < rq.n;
@@ -176,7 +176,7 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     };
     auto advance = [&]() {
         ++rq.j;
-        rq.wp += SF * 64;
+        rq.wp += (RS == 2 ? FV_FRAGS : 2 * FV_FRAGS) * 64;
         rq.xp += 2 * SF * Tp;
         if (rq.j >= rq.n3) enter_slice(rq.s + 1);   // also taken, harmlessly, once the stream has ended
     };

@@ -529,7 +529,9 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
         const int rem = u1 - gi * a.NB;
         nb = (rem < a.NB ? rem : a.NB) - b0;
     };
-    const uint4* __restrict__ wbase = a.Wt + (size_t)wave * a.NB * (FV_FRAGS * 64) + lane;
+    // weights are tiled [strip pair][half K batch][2 strips][4 frags]: this wavefront's strip is strip (wave % 2) of pair
+    // gi * 2 + wave / 2; a K batch of it is two 4 KiB pieces 8 KiB apart, and batches follow each other 16 KiB apart
+    const uint4* __restrict__ wbase = a.Wt + ((size_t)(wave >> 1) * (2 * a.NB) * 2 + (wave & 1)) * (4 * 64) + lane;
     const size_t group_stride = (size_t)R * a.NB * (FV_FRAGS * 64);
     const uint4* const zeros = a.zeros;
 
@@ -543,12 +545,12 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
             int gi, b0, nb;
             segment(rs, gi, b0, nb);
             rn = nb; rn3 = (nb + 2) / 3 * 3;
-            wp = wbase + (size_t)gi * group_stride + (size_t)b0 * (FV_FRAGS * 64);
+            wp = wbase + (size_t)gi * group_stride + (size_t)b0 * (2 * FV_FRAGS * 64);
             xp = a.X + (size_t)b0 * CV + tid;
         }
     };
     auto advance = [&]() {
-        ++rj; wp += FV_FRAGS * 64; xp += CV;
+        ++rj; wp += 2 * FV_FRAGS * 64; xp += CV;
         if (rj >= rn3) enter(rs + 1);
     };
     auto load_w = [&](uint4 (&dst)[FV_FRAGS]) {
@@ -556,7 +558,7 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
         const uint4* pw = live ? wp : a.Wt;
         const int st = live ? 64 : 0;
 #pragma unroll
-        for (int f = 0; f < FV_FRAGS; ++f) dst[f] = pw[f * st];
+        for (int f = 0; f < FV_FRAGS; ++f) dst[f] = pw[(f < 4 ? f : f + 4) * st];
     };
     auto load_x = [&](u32x4 (&dst)[XV]) {
         const bool live = rj < rn;
@@ -634,7 +636,7 @@ __global__ __launch_bounds__(64 * FV_R, 1) void k_gemm(GemmArgs a) {
         gemm_compute<EL, TB>(w[S], lds + par * CV, acc, lane, [&](int f) {                              \
             _Pragma("unroll") for (int i_ = f * NLD / FV_FRAGS; i_ < (f + 1) * NLD / FV_FRAGS; ++i_) {  \
                 if (i_ < XV) xr[i_] = *(const u32x4*)(px_ + i_ * sx_);                                  \
-                else w[S2][i_ - XV] = pw_[(i_ - XV) * sw_];                                             \
+                else w[S2][i_ - XV] = pw_[((i_ - XV) < 4 ? (i_ - XV) : (i_ - XV) + 4) * sw_];                                             \
             }                                                                                           \
         });                                                                                             \
         FV_PH(0)                                                                                        \
@@ -1205,9 +1207,13 @@ __global__ __launch_bounds__(256) void k_tile(TileArgs a) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int lane = idx & 63;
-    const size_t fb = idx >> 6;
-    const int frag = (int)(fb % ((size_t)a.NB * FV_FRAGS));
-    const int strip = (int)(fb / ((size_t)a.NB * FV_FRAGS));
+    // output order [strip pair][half K batch][strip of the pair][4 frags][64 lanes]
+    const size_t tile = idx >> 6;
+    const int ff = (int)(tile & 3), r = (int)((tile >> 2) & 1);
+    const size_t pj = tile >> 3;
+    const int j = (int)(pj % ((size_t)2 * a.NB));
+    const int strip = 2 * (int)(pj / ((size_t)2 * a.NB)) + r;
+    const int frag = 4 * j + ff;
     const int m = lane & 31, g = lane >> 5;
     const int k0 = frag * 2 * E + g * E;
     const void* src = nullptr;
