@@ -139,6 +139,32 @@ int fv_verify_tree(fv_ctx* ctx, const int32_t* tree_tokens, const int32_t* paren
                    const int32_t* depth, int32_t n_nodes,
                    int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token);
 
+/* One NON-greedy verification step: multi-step speculative sampling over the tree (Appendix "Tree
+ * Structure": in a non-greedy setting a node's children are sampled instead of being the top-m
+ * tokens; section "Custom-Designed Decoding Tree": the LLM verifies the tree in the SpecInfer manner).
+ * The forward pass, K/V compaction, state update and read-back are those of fv_verify_tree; only the
+ * acceptance rule differs.  With p = softmax(logits[node] / temperature) at the current node (the root
+ * first), its children are tried in index order: child c with token x is accepted with probability
+ * min(1, p[x] / q[x]) -- the test is u_accept[c] * q[x] <= p[x] -- and becomes the current node; on
+ * rejection p becomes the normalised positive part of p - q.  When no child is accepted (or there is
+ * none) next_token is drawn from what is left of p: the first token id v with cumsum(p)[v] >
+ * u_sample[node].  Every emitted token is then distributed as the target's own sampling.
+ *   temperature      > 0 (host value)
+ *   dev_draft_probs  DEVICE pointer, fp32 row-major [n_nodes][vocab]: row i is the distribution the
+ *                    drafter drew node i's children from (rows of leaves are not read); owned by the
+ *                    caller, only read.  NULL: every child is its own point-mass proposal (q[x] = 1),
+ *                    the right rule for deterministic (top-m) children: accept with probability p[x],
+ *                    else strike x from p.
+ *   u_accept, u_sample   HOST arrays of n_nodes doubles in [0, 1], drawn by the caller (the library
+ *                    draws no random numbers): u_accept[c] decides node c, u_sample[i] the draw at node i.
+ * The decisions are taken in fp64 from the fp32 logits.  Errors as fv_verify_tree, plus FV_E_BAD_ARG for
+ * a bad temperature or a uniform outside [0, 1]. */
+int fv_verify_tree_sampled(fv_ctx* ctx, const int32_t* tree_tokens, const int32_t* parent_idx,
+                           const int32_t* depth, int32_t n_nodes,
+                           float temperature, const float* dev_draft_probs,
+                           const double* u_accept, const double* u_sample,
+                           int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token);
+
 /* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc inside the step): fv_verify_tree with every scratch buffer of the step's
  * kernels (stream-K partial tiles and tickets, attention key-split partials and tickets) taken from

@@ -391,6 +391,20 @@ class Oracle:
                    features=self.last_hidden[out["path"]].copy())
         return out
 
+    def verify_tree_sampled(self, tokens, parent, depth, temperature, u_accept, u_sample, draft_probs=None):
+        """One non-greedy verification step: the tree's logits as in verify_tree, acceptance by
+        sampled_accept(), then the same compaction and state update."""
+        s, L = self.s, self.L
+        if self.pending is None:
+            raise TreeVerifyError("no prefill")
+        self.check_tree(tokens, parent, depth, s.vocab, self.pending, L, self.K.shape[1])
+        logits, newK, newV = self.tree_logits(tokens, parent, depth)
+        out = sampled_accept(logits, tokens, parent, depth, L, temperature, u_accept, u_sample, draft_probs)
+        self.commit(out, newK, newV)
+        out.update(logits=logits, mask=ancestor_mask(parent), tree_k=newK, tree_v=newV,
+                   features=self.last_hidden[out["path"]].copy())
+        return out
+
     def commit(self, decision, newK, newV):
         """Compaction and state update: the K/V of path node j goes to cache slot L + j, the
         committed length grows by accepted_len + 1 and the bonus token becomes the next root."""

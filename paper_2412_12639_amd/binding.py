@@ -61,6 +61,8 @@ def load_library():
         "fv_prefill": [vp, i32p, C.c_int32, i32p],
         "fv_verify_tree": [vp, i32p, i32p, i32p, C.c_int32, i32p, i32p, i32p],
         "fv_verify_tree_noalloc": [vp, i32p, i32p, i32p, C.c_int32, i32p, i32p, i32p],
+        "fv_verify_tree_sampled": [vp, i32p, i32p, i32p, C.c_int32, C.c_float, vp, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                   i32p, i32p, i32p],
         "fv_rollback": [vp, C.c_int32, C.c_int32],
         "fv_get_state": [vp, i32p, i32p],
         "fv_get_tree_mask": [vp, C.POINTER(C.c_uint64), C.c_int32],
@@ -204,6 +206,31 @@ class FalconVerifier:
         fn = self.lib.fv_verify_tree_noalloc if noalloc else self.lib.fv_verify_tree
         self._chk(fn(self.ctx, tp, pp, dp, len(t), C.byref(a), acc.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nxt)),
                   "fv_verify_tree_noalloc" if noalloc else "fv_verify_tree")
+        self.last_n = len(t)
+        return a.value, acc[:a.value].copy(), nxt.value
+
+    def verify_tree_sampled(self, tokens, parent, depth, temperature, u_accept, u_sample, draft_probs=None):
+        """Non-greedy step.  draft_probs: None, or a torch float32 tensor [n_nodes, vocab] on this device
+        (only its data pointer is passed on)."""
+        t, tp = _i32(tokens)
+        p, pp = _i32(parent)
+        d, dp = _i32(depth)
+        ua = np.ascontiguousarray(u_accept, dtype=np.float64)
+        us = np.ascontiguousarray(u_sample, dtype=np.float64)
+        if not (len(t) == len(p) == len(d) == len(ua) == len(us)):
+            raise ValueError("tokens, parent, depth, u_accept and u_sample must have the same length")
+        qptr = None
+        if draft_probs is not None:
+            if not (draft_probs.is_cuda and draft_probs.is_contiguous() and tuple(draft_probs.shape) == (len(t), self.shape.vocab)
+                    and str(draft_probs.dtype) == "torch.float32"):
+                raise ValueError("draft_probs must be a contiguous float32 device tensor [n_nodes, vocab]")
+            qptr = C.c_void_p(draft_probs.data_ptr())
+        a, nxt = C.c_int32(-1), C.c_int32(-1)
+        acc = np.zeros(max(1, len(t)), dtype=np.int32)
+        self._chk(self.lib.fv_verify_tree_sampled(self.ctx, tp, pp, dp, len(t), C.c_float(temperature), qptr,
+                                                  ua.ctypes.data_as(C.POINTER(C.c_double)), us.ctypes.data_as(C.POINTER(C.c_double)),
+                                                  C.byref(a), acc.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(nxt)),
+                  "fv_verify_tree_sampled")
         self.last_n = len(t)
         return a.value, acc[:a.value].copy(), nxt.value
 

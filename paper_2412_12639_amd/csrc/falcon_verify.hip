@@ -186,6 +186,8 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     L.off_am = take(FV_MAX_TREE * 4);
     L.off_res = take(sizeof(FvResult));
     L.off_feat = take((size_t)FV_MAX_TREE * c.hidden * 4);
+    L.off_unif = take((size_t)2 * FV_MAX_TREE * 8);
+    L.off_pwork = take((size_t)L.Vpad * 8);
     L.off_kvread = take((size_t)2 * 64 * kvd * 4);
     size_t st = (size_t)(qd + 2 * kvd) * c.hidden;
     const size_t cands[4] = {(size_t)c.hidden * qd, (size_t)2 * c.ffn * c.hidden, (size_t)c.hidden * c.ffn,
@@ -338,6 +340,7 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipHostMalloc((void**)&c->h_res, sizeof(FvResult), hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
+    if (hipHostMalloc((void**)&c->h_unif, 2 * FV_MAX_TREE * 8, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipEventCreate(&c->ev0) != hipSuccess || hipEventCreate(&c->ev1) != hipSuccess) return fail(FV_E_HIP);
     // zero everything except the weights (they are written by fv_init_weights): pad lanes of
     // activations and never-written cache slots must hold finite values
@@ -395,6 +398,7 @@ void fv_destroy(fv_ctx* c) {
     if (!c) return;
     if (c->h_in) (void)hipHostFree(c->h_in);
     if (c->h_res) (void)hipHostFree(c->h_res);
+    if (c->h_unif) (void)hipHostFree(c->h_unif);
     if (c->ev0) (void)hipEventDestroy(c->ev0);
     if (c->ev1) (void)hipEventDestroy(c->ev1);
     for (hipEvent_t e : c->pev) (void)hipEventDestroy(e);
@@ -442,11 +446,11 @@ int fv_prefill(fv_ctx* c, const int32_t* tokens, int32_t n, int32_t* next_token)
 }
 
 static int verify_tree_impl(fv_ctx* c, const int32_t* tok, const int32_t* parent, const int32_t* depth, int32_t n,
-                            int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token) {
+                            int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token, StepMode mode = STEP_VERIFY) {
     memcpy(c->h_in, tok, (size_t)n * 4);
     memcpy(c->h_in + FV_MAX_TREE, parent, (size_t)n * 4);
     memcpy(c->h_in + 2 * FV_MAX_TREE, depth, (size_t)n * 4);
-    int rc = run_step_any(c, n, STEP_VERIFY);
+    int rc = run_step_any(c, n, mode);
     if (rc) return rc;
     const FvResult& r = *c->h_res;
     if (r.accepted_len == FV_SCAN_NONFINITE) return FV_E_NONFINITE;
@@ -490,6 +494,24 @@ int fv_verify_tree_noalloc(fv_ctx* c, const int32_t* tok, const int32_t* parent,
     c->scr = &c->scr_arena;
     c->profiling = prof;
     return rc;
+}
+
+int fv_verify_tree_sampled(fv_ctx* c, const int32_t* tok, const int32_t* parent, const int32_t* depth, int32_t n,
+                           float temperature, const float* dev_draft_probs, const double* u_accept, const double* u_sample,
+                           int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token) {
+    if (!c || !accepted_len || !accepted_tokens || !next_token || !u_accept || !u_sample) return FV_E_BAD_ARG;
+    if (!(temperature > 0.f) || !(temperature < INFINITY)) return FV_E_BAD_ARG;
+    if (!c->weights_set || !c->prefilled) return FV_E_NO_PREFILL;
+    int rc = validate_tree(c->cfg, tok, parent, depth, n, c->pending, c->cur_len, true);
+    if (rc) return rc;
+    for (int i = 0; i < n; ++i)   // uniforms in [0, 1]; NaN is refused too
+        if (!(u_accept[i] >= 0.0 && u_accept[i] <= 1.0) || !(u_sample[i] >= 0.0 && u_sample[i] <= 1.0)) return FV_E_BAD_ARG;
+    memcpy(c->h_unif, u_accept, (size_t)n * 8);
+    memcpy(c->h_unif + FV_MAX_TREE, u_sample, (size_t)n * 8);
+    c->sample_inv_temperature = 1.0 / (double)temperature;
+    c->sample_draft = dev_draft_probs;
+    c->scr = &c->scr_arena;
+    return verify_tree_impl(c, tok, parent, depth, n, accepted_len, accepted_tokens, next_token, STEP_VERIFY_SAMPLED);
 }
 
 int fv_rollback(fv_ctx* c, int32_t new_len, int32_t pending_root) {

@@ -55,6 +55,7 @@ struct Layout {
     size_t off_stepin = 0, off_mask = 0, off_pos = 0, off_rope = 0, off_am = 0, off_res = 0;
     size_t off_kvread = 0, off_stage = 0, stage_bytes = 0;
     size_t off_apart = 0, off_atick = 0, off_zeros = 0, off_feat = 0;
+    size_t off_unif = 0, off_pwork = 0;   // non-greedy acceptance: uniforms [2][256] fp64, working distribution [Vpad] fp64
     size_t total = 0;
 };
 
@@ -67,7 +68,7 @@ inline int pad_tokens(int n) {   // token count padded to 32, 64, 128 or 256
 
 // GEMM kernel used up to 64 tokens (above that always the shared-activation kernel)
 enum GemmKind { GEMM_SHARED = 0, GEMM_DIRECT = 1, GEMM_PAIRED = 3 };
-enum StepMode { STEP_VERIFY = 0, STEP_PREFILL_MID = 1, STEP_PREFILL_LAST = 2 };
+enum StepMode { STEP_VERIFY = 0, STEP_PREFILL_MID = 1, STEP_PREFILL_LAST = 2, STEP_VERIFY_SAMPLED = 3 };
 
 // Device memory the kernels of a step use beyond inputs and outputs: stream-K partial tiles and
 // their tickets, attention key-split partials and their tickets.
@@ -90,6 +91,9 @@ struct fv_ctx {
     bool last_was_verify = false;
     int32_t* h_in = nullptr;      // pinned [3][256]
     FvResult* h_res = nullptr;    // pinned
+    double* h_unif = nullptr;     // pinned [2][256]: u_accept, u_sample of a non-greedy step
+    double sample_inv_temperature = 1.0;      // of the non-greedy step being run
+    const float* sample_draft = nullptr;      // device [n][vocab] or null
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     float last_ms = 0.f;
     bool profiling = false;

@@ -1166,6 +1166,147 @@ static __global__ __launch_bounds__(256) void k_scan(ScanArgs a) {
     }
 }
 
+// ============================================================================ non-greedy acceptance
+// Multi-step speculative sampling over the tree (the non-greedy setting of the paper's Appendix
+// "Tree Structure"; verification in the SpecInfer manner, section "Custom-Designed Decoding Tree").
+// Single block.  Starting at the root with w = exp((logits[node] - max) / temperature): the children of
+// the current node are tried in index order; child c with token x is accepted iff
+// u_accept[c] * q[x] * sum(w) <= w[x]; on rejection w becomes the positive part of w - sum(w) * q and the
+// next child is tried against it.  q is row `node` of draft_probs, or a point mass on x if draft_probs
+// is null (then rejection just strikes x from w).  When no child is accepted the next token is the first
+// v with cumsum(w)[v] > u_sample[node] * sum(w).  All of it in fp64 (the decisions are thresholds on sums
+// of 32000 terms; fp64 keeps both sides of a comparison with a CPU implementation within ~1e-13 of each
+// other), in a fixed order, so the result is reproducible.
+struct SampledArgs {
+    const int32_t* tok_in;     // [3][cap]: tokens, parent, depth
+    int cap, T;
+    const float* logits;       // [Tp][Vpad]
+    int V, Vpad;
+    double inv_temperature;
+    const float* draft_probs;  // [T][V] or null
+    const double* u_accept;    // [T]
+    const double* u_sample;    // [T]
+    double* work;              // [Vpad]
+    FvResult* res;
+};
+
+#define FV_SAMPLED_THREADS 1024
+
+// sum of one value per thread over the block, in a fixed order; every thread gets the result
+__device__ __forceinline__ double block_sum_f64(double v, double* red) {
+    const int tid = threadIdx.x;
+    red[tid] = v;
+    __syncthreads();
+    for (int w = FV_SAMPLED_THREADS / 2; w > 0; w >>= 1) {
+        if (tid < w) red[tid] += red[tid + w];
+        __syncthreads();
+    }
+    const double r = red[0];
+    __syncthreads();
+    return r;
+}
+
+static __global__ __launch_bounds__(FV_SAMPLED_THREADS) void k_accept_sampled(SampledArgs a) {
+    __shared__ double red[FV_SAMPLED_THREADS];
+    __shared__ int s_flag, s_pick;
+    __shared__ float s_maxf[FV_SAMPLED_THREADS / 64];
+    const int tid = threadIdx.x;
+    const int32_t* tok = a.tok_in;
+    const int32_t* parent = a.tok_in + a.cap;
+    const int chunk = (a.V + FV_SAMPLED_THREADS - 1) / FV_SAMPLED_THREADS;   // contiguous tokens per thread
+    const int v0 = tid * chunk, v1 = (v0 + chunk < a.V) ? v0 + chunk : a.V;
+    int cur = 0, len = 0, next_token = -1;
+    bool bad = false;
+    if (tid == 0) a.res->path[0] = 0;
+    for (int hop = 0; hop < a.T && next_token < 0 && !bad; ++hop) {
+        const float* row = a.logits + (size_t)cur * a.Vpad;
+        // ---- w = exp((row - max) / temperature), S = sum(w)
+        float mx = -INFINITY;
+        bool nf = false;
+        for (int v = v0; v < v1; ++v) { const float x = row[v]; nf = nf || !(__builtin_fabsf(x) < INFINITY); mx = fmaxf(mx, x); }
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        if (tid == 0) s_flag = 0;
+        __syncthreads();
+        if (nf) s_flag = 1;
+        if ((tid & 63) == 0) s_maxf[tid >> 6] = mx;
+        __syncthreads();
+        if (s_flag) { bad = true; break; }
+        for (int k = 0; k < FV_SAMPLED_THREADS / 64; ++k) mx = fmaxf(mx, s_maxf[k]);
+        const double zmax = (double)mx * a.inv_temperature;
+        auto fill = [&]() {
+            double ls = 0.0;
+            for (int v = v0; v < v1; ++v) { const double w = exp((double)row[v] * a.inv_temperature - zmax); a.work[v] = w; ls += w; }
+            return ls;
+        };
+        double S = block_sum_f64(fill(), red);
+        // ---- the children of cur, in index order
+        int taken = -1;
+        for (int c = cur + 1; c < a.T && taken < 0; ++c) {
+            if (parent[c] != cur) continue;            // uniform: every thread reads the same value
+            const int x = tok[c];
+            const double qx = a.draft_probs ? (double)a.draft_probs[(size_t)cur * a.V + x] : 1.0;
+            __syncthreads();                            // a.work[x] as left by the previous child's update
+            const double lhs = a.u_accept[c] * qx * S, rhs = a.work[x];
+            if (lhs <= rhs) { taken = c; break; }
+            __syncthreads();                            // everyone has read work[x] before it changes
+            double ls = 0.0;
+            if (a.draft_probs) {
+                const float* q = a.draft_probs + (size_t)cur * a.V;
+                for (int v = v0; v < v1; ++v) { const double w = fmax(a.work[v] - S * (double)q[v], 0.0); a.work[v] = w; ls += w; }
+            } else {
+                for (int v = v0; v < v1; ++v) { if (v == x) a.work[v] = 0.0; ls += a.work[v]; }
+            }
+            double S2 = block_sum_f64(ls, red);
+            if (!(S2 > 0.0)) S2 = block_sum_f64(fill(), red);   // nothing left besides what was rejected (probability zero): keep the last p
+            S = S2;
+        }
+        if (taken >= 0) {
+            ++len;
+            if (tid == 0) { a.res->path[len] = taken; a.res->accepted_tokens[len - 1] = tok[taken]; }
+            cur = taken;
+            continue;
+        }
+        // ---- draw: the first v with cumsum(w)[v] > target
+        __syncthreads();
+        const double target = a.u_sample[cur] * S;
+        double ls = 0.0;
+        for (int v = v0; v < v1; ++v) ls += a.work[v];
+        // inclusive prefix over the threads' chunk sums (fixed order)
+        red[tid] = ls;
+        __syncthreads();
+        for (int off = 1; off < FV_SAMPLED_THREADS; off <<= 1) {
+            const double add = (tid >= off) ? red[tid - off] : 0.0;
+            __syncthreads();
+            red[tid] += add;
+            __syncthreads();
+        }
+        const double before = red[tid] - ls;
+        if (tid == 0) s_pick = 0x7fffffff;
+        __syncthreads();
+        if (ls > 0.0 && before <= target && target < red[tid]) {
+            double c = before;
+            int pick = -1;
+            for (int v = v0; v < v1; ++v) { c += a.work[v]; if (c > target) { pick = v; break; } }
+            if (pick < 0) for (int v = v1 - 1; v >= v0; --v) if (a.work[v] > 0.0) { pick = v; break; }   // rounding inside the chunk
+            if (pick >= 0) atomicMin(&s_pick, pick);
+        }
+        __syncthreads();
+        if (s_pick == 0x7fffffff) {
+            // target at or beyond the total (u_sample ~ 1 and rounding): the last token that has any mass
+            for (int v = v1 - 1; v >= v0; --v) if (a.work[v] > 0.0) { atomicMax(&s_flag, v + 1); break; }
+            __syncthreads();
+            next_token = s_flag - 1;
+        } else {
+            next_token = s_pick;
+        }
+    }
+    if (tid == 0) {
+        if (bad || next_token < 0) { a.res->accepted_len = FV_SCAN_NONFINITE; a.res->next_token = -1; a.res->best = 0; }
+        else { a.res->accepted_len = len; a.res->next_token = next_token; a.res->best = cur; }
+        a.res->pad = 0;
+    }
+}
+
 // ============================================================================ KV compaction
 // For every layer and KV head: cache slot L + j <- cache slot L + path[j], j = 0..a.
 // Tree K/V were written at slots L + node index; path[j] >= j, and thread e moves element e

@@ -108,6 +108,8 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
     c->pev_used = 0;
 
     HIPCHK(hipMemcpyAsync(c->at<int32_t>(ly.off_stepin), c->h_in, 3 * FV_MAX_TREE * 4, hipMemcpyHostToDevice, st));
+    if (mode == STEP_VERIFY_SAMPLED)
+        HIPCHK(hipMemcpyAsync(c->at<double>(ly.off_unif), c->h_unif, 2 * FV_MAX_TREE * 8, hipMemcpyHostToDevice, st));
     HIPCHK(hipEventRecord(c->ev0, st));
     {
         PhaseTimer pt(c, FV_PH_OTHER);
@@ -203,11 +205,22 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         ArgmaxArgs am;
         am.logits = c->at<float>(ly.off_logits); am.am = c->at<int32_t>(ly.off_am); am.V = cf.vocab; am.Vpad = ly.Vpad;
         hipLaunchKernelGGL(k_argmax, dim3(T), dim3(256), 0, st, am);
+        if (mode == STEP_VERIFY_SAMPLED) {
+            SampledArgs sa;
+            sa.tok_in = c->at<int32_t>(ly.off_stepin); sa.cap = FV_MAX_TREE; sa.T = T;
+            sa.logits = c->at<float>(ly.off_logits); sa.V = cf.vocab; sa.Vpad = ly.Vpad;
+            sa.inv_temperature = c->sample_inv_temperature; sa.draft_probs = c->sample_draft;
+            sa.u_accept = c->at<double>(ly.off_unif); sa.u_sample = sa.u_accept + FV_MAX_TREE;
+            sa.work = c->at<double>(ly.off_pwork); sa.res = c->at<FvResult>(ly.off_res);
+            hipLaunchKernelGGL(k_accept_sampled, dim3(1), dim3(FV_SAMPLED_THREADS), 0, st, sa);
+        }
         if (mode == STEP_VERIFY) {
             ScanArgs sa;
             sa.tok_in = c->at<int32_t>(ly.off_stepin); sa.cap = FV_MAX_TREE; sa.T = T;
             sa.mask = c->at<uint64_t>(ly.off_mask); sa.am = c->at<int32_t>(ly.off_am); sa.res = c->at<FvResult>(ly.off_res);
             hipLaunchKernelGGL(k_scan, dim3(1), dim3(256), 0, st, sa);
+        }
+        if (mode == STEP_VERIFY || mode == STEP_VERIFY_SAMPLED) {
             CompactArgs ca;
             ca.kcache = c->at<void>(ly.off_k); ca.vcache = c->at<void>(ly.off_v); ca.res = c->at<FvResult>(ly.off_res);
             ca.L = L; ca.S_pad = ly.S_pad;
@@ -224,7 +237,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         HIPCHK(hipGetLastError());
     }
     HIPCHK(hipEventRecord(c->ev1, st));
-    if (mode == STEP_VERIFY)
+    if (mode == STEP_VERIFY || mode == STEP_VERIFY_SAMPLED)
         HIPCHK(hipMemcpyAsync(c->h_res, c->at<FvResult>(ly.off_res), sizeof(FvResult), hipMemcpyDeviceToHost, st));
     else if (mode == STEP_PREFILL_LAST)
         HIPCHK(hipMemcpyAsync(&c->h_res->next_token, c->at<int32_t>(ly.off_am) + (T - 1), 4, hipMemcpyDeviceToHost, st));
@@ -240,7 +253,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         }
     }
     c->last_T = T; c->last_Tp = Tp; c->last_L = L;
-    c->last_was_verify = (mode == STEP_VERIFY);
+    c->last_was_verify = (mode == STEP_VERIFY || mode == STEP_VERIFY_SAMPLED);
     return FV_OK;
 }
 
