@@ -52,38 +52,58 @@ def build_tree(fi, gpu, shape, n_nodes, branching, plant_len, prefix_len, root, 
     return tokens, parent, depth, greedy
 
 
+def host_cpu():
+    """(logical cores visible to this process, CPU model string) of the box the benchmark runs on."""
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    return cores, model
+
+
 def cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root, sample_layers, full_bytes):
-    """The oracle as it stands, timed on this host on a bounded sample: the same step on the
-    first `sample_layers` layers (+ final norm and LM head) of the same weights; scaled to the
-    full model by algorithmic bytes (all of the step's work is proportional to them)."""
+    """The oracle as it stands (numpy, fp64), timed on this host on ONE verify_tree call of the same tree.
+    sample_layers == all layers: the whole step is timed, nothing is extrapolated.  The oracle's prompt pass (minutes at
+    this size, and not part of the timed quantity) is skipped: its K/V cache is filled with N(0, 1) values instead, which
+    changes the numbers the step computes but not one operation of it.  Fewer layers: the same step on a model cut to its
+    first layers (+ final norm and LM head), scaled to the full model by algorithmic bytes, and labelled as an estimate."""
     from oracle import falcon_oracle as fo
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    sub, subw = fi.sub_model(shape, weights, sample_layers)
+    cores, model = host_cpu()
+    full = sample_layers >= shape.n_layers
+    sub, subw = (shape, weights) if full else fi.sub_model(shape, weights, sample_layers)
     L, T = len(prefix), len(tokens)
     o = fo.Oracle(sub, subw, max_seq=L + T + 8, dtype=np.float64)
+    rng = np.random.Generator(np.random.Philox(key=[7, 7200]))
+    o.K[:, :L] = rng.standard_normal(o.K[:, :L].shape)
+    o.V[:, :L] = rng.standard_normal(o.V[:, :L].shape)
+    o.rollback(L, int(tokens[0]))
     t0 = time.time()
-    o.prefill(prefix)
-    t_prefill = time.time() - t0
-    o.rollback(L, int(tokens[0]))   # same root token as the GPU step (the sub-model's own greedy token differs)
-    times = []
-    for _ in range(2):
-        t0 = time.time()
-        o.verify_tree(tokens, parent, depth)
-        times.append(time.time() - t0)
-        o.rollback(L, int(tokens[0]))
-    t_s = min(times)
-    scale = full_bytes / sub.step_bytes(L, T)
+    o.verify_tree(tokens, parent, depth)
+    t_s = time.time() - t0
+    scale = 1.0 if full else full_bytes / sub.step_bytes(L, T)
     t_full = t_s * scale
+    what = (f"the whole step, all {shape.n_layers} layers + LM head, timed once: {t_s:.1f} s" if full else
+            f"ESTIMATE: the first {sample_layers} of {shape.n_layers} layers + LM head timed ({t_s:.2f} s), "
+            f"x{scale:.2f} by algorithmic bytes -> {t_full:.1f} s per full step")
     return {
-        "value": T / t_full, "unit": "verified tree tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"numpy fp64 oracle, verify_tree on the first {sample_layers} of {shape.n_layers} layers + LM head "
-                  f"({t_s:.2f} s measured, x{scale:.2f} by algorithmic bytes -> {t_full:.1f} s per full step; "
-                  f"oracle prefill of the sample took {t_prefill:.1f} s)",
-        "ms_per_step_est": t_full * 1e3,
+        "value": T / t_full, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"numpy fp64 oracle, one verify_tree call on the benchmark's tree ({T} nodes, prefix {L}); {what}; the prefix "
+                  f"K/V cache holds N(0,1) values instead of a prompt pass (same operations, other numbers)",
+        "ms_per_step": t_full * 1e3, "extrapolated": not full,
+        "host": {"logical_cores_available": cores, "blas_threads_used": int(threads), "cpu_model": model},
     }
 
 
@@ -152,17 +172,40 @@ def decode_loop(fi, gpu, shape, L, root, n_nodes, branching, n_tokens, p_accept,
     }
 
 
+def kernel_source_hash():
+    """sha256 over the library's HIP sources (what the counter runs under profiles/ were measured on)."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2412_12639_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(kname, args, shape):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs
     (profiles/traffic_*.md: FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), if one
-    exists for exactly this workload and kernel; else None."""
+    exists for exactly this workload and kernel AND was measured on the kernel sources as they are
+    now (the file records their hash); else None."""
     path = os.path.join(ROOT, "profiles", f"traffic_{shape.name}_prefix{args.prefix}_tree{args.nodes}.md")
     if args.layers or not os.path.exists(path):
-        return None
-    for line in open(path):
+        return None, None
+    text = open(path).read().splitlines()
+    src = [l.split("=")[1].split()[0] for l in text if l.startswith("KERNEL_SOURCE_SHA256_16")]
+    if not src or src[0] != kernel_source_hash():
+        return None, (src[0] if src else None)
+    for line in text:
         if line.startswith("TRAFFIC_BYTES_PER_LAUNCH") and kname.split()[0] in line:
-            return float(line.split("=")[1].split()[0])
-    return None
+            return float(line.split("=")[1].split()[0]), src[0]
+    return None, src[0]
+
+
+def stream_ceiling(gpu):
+    """Context for the roofline: what a plain streaming read of the same weights reaches on this machine."""
+    return {"value": gpu.stream_read_gbs(4), "unit": "GB/s",
+            "how": "fv_stream_read: the library's pure-read kernel (256 workgroups, contiguous 16-byte loads) over the first "
+                   "4 GiB of the tiled weights, 4 passes after one untimed"}
 
 
 def main():
@@ -178,7 +221,8 @@ def main():
                     help="children per level, or 'random' (per-level branching uniform in [1, 8], depth <= 8, seeded)")
     ap.add_argument("--plant", type=int, default=3)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--cpu-layers", type=int, default=2, help="layers in the oracle's CPU-baseline sample (0 = skip)")
+    ap.add_argument("--cpu-layers", type=int, default=-1,
+                    help="layers in the oracle's CPU-baseline sample: -1 = all (the whole step, about half a minute), 0 = skip")
     ap.add_argument("--profile-steps", type=int, default=10)
     ap.add_argument("--loop-tokens", type=int, default=48,
                     help="tokens of the multi-step decoding comparison (tree verification with a synthetic drafter "
@@ -319,9 +363,13 @@ def main():
                                   "note": "algorithmic K/V bytes over the per-launch HIP-event time of k_attn (profiling pass)"}
     if args.loop_tokens > 0:
         out["decode_loop"] = decode_loop(fi, gpu, shape, L, root, T, branching, args.loop_tokens, args.loop_p, args.seed)
-    traffic = measured_traffic(kname, args, shape)
-    if traffic is not None:
-        out["roofline"]["traffic"] = traffic
+    traffic, traffic_src = measured_traffic(kname, args, shape)
+    out["roofline"]["traffic"] = traffic
+    out["roofline"]["traffic_note"] = (
+        "FETCH_SIZE + WRITE_SIZE per launch from profiles/traffic_*.md, measured on these kernel sources" if traffic is not None else
+        f"not reported: profiles/ holds no counter run for this workload on the current kernel sources "
+        f"(sources {kernel_source_hash()}, counter run {traffic_src})")
+    out["stream_ceiling"] = stream_ceiling(gpu)
     if args.layers:
         out["invalid"] = "model truncated with --layers (debug run)"
     if args.calib_copy_mb > 0:
@@ -332,10 +380,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         log(f"calibration: 3 device copies of {n} bytes (reads {n}, writes {n} each)")
-    if args.cpu_layers > 0:
-        log("timing the CPU oracle on a bounded sample ...")
-        out["cpu_baseline"] = cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root,
-                                           min(args.cpu_layers, shape.n_layers), step_bytes)
+    if args.cpu_layers != 0:
+        log("timing the CPU oracle on one verify_tree call ...")
+        n_cpu = shape.n_layers if args.cpu_layers < 0 else min(args.cpu_layers, shape.n_layers)
+        out["cpu_baseline"] = cpu_baseline(fi, shape, weights, prefix, tokens, parent, depth, root, n_cpu, step_bytes)
     else:
         out["cpu_baseline"] = None
     gpu.close()

@@ -223,6 +223,12 @@ int fv_debug_read_activation(fv_ctx* ctx, int32_t which, int32_t n_nodes, float*
 
 /* ---- measurement ---- */
 
+/* Context for the roofline figures: the rate in GB/s (1e9 bytes) at which a plain streaming-read kernel of
+ * the library (one workgroup per compute unit, contiguous 16-byte loads) reads the context's tiled weights
+ * (the first 4 GiB of them at most) `passes` times (1..64) on the context's stream, after one untimed pass.
+ * Writes nothing the step uses.  *gbytes_per_s: host output. */
+int fv_stream_read(fv_ctx* ctx, int32_t passes, float* gbytes_per_s);
+
 /* When enabled, each subsequent step brackets its kernels with HIP events on the
  * context's stream and accumulates per-phase device time.  Off by default (the events
  * cost launch gaps). */

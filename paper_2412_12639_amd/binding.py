@@ -72,6 +72,7 @@ def load_library():
         "fv_get_features": [vp, C.POINTER(C.c_float), C.c_int32],
         "fv_read_kv": [vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
         "fv_debug_read_activation": [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float)],
+        "fv_stream_read": [vp, C.c_int32, C.POINTER(C.c_float)],
         "fv_set_profiling": [vp, C.c_int32],
         "fv_get_phase_times": [vp, C.POINTER(C.c_float), i32p],
         "fv_last_step_ms": [vp, C.POINTER(C.c_float)],
@@ -303,6 +304,12 @@ class FalconVerifier:
         n = (C.c_int32 * len(PHASES))()
         self._chk(self.lib.fv_get_phase_times(self.ctx, ms, n), "fv_get_phase_times")
         return {PHASES[i]: (ms[i], n[i]) for i in range(len(PHASES))}
+
+    def stream_read_gbs(self, passes: int = 4) -> float:
+        """GB/s of the library's plain streaming-read kernel over the tiled weights (roofline context)."""
+        v = C.c_float()
+        self._chk(self.lib.fv_stream_read(self.ctx, passes, C.byref(v)), "fv_stream_read")
+        return v.value
 
     def last_step_ms(self) -> float:
         v = C.c_float()

@@ -28,6 +28,22 @@ static __global__ void k_fill_u32(uint32_t* p, uint32_t v, size_t n) {
     if (i < n) p[i] = v;
 }
 
+// plain streaming read (measurement aid, fv_stream_read): one workgroup per compute unit, each wavefront walks its own
+// contiguous share with sixteen 16-byte loads per lane in flight
+static __global__ __launch_bounds__(256) void k_stream_read(const uint4* p, size_t n16, uint4* sink) {
+    const size_t per_wave = n16 / ((size_t)gridDim.x * 4);
+    const uint4* q = p + ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * per_wave + (threadIdx.x & 63);
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i = 0; i + 16 * 64 <= per_wave; i += 16 * 64) {
+        uint4 v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = q[i + k * 64];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { acc.x ^= v[k].x; acc.y ^= v[k].y; acc.z ^= v[k].z; acc.w ^= v[k].w; }
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[threadIdx.x] = acc;   // keeps the loads alive; practically never taken
+}
+
 // Device address of the current device's copy of `scratch` (looked up once per device).
 static int static_scratch_ptr(char** out) {
     int dev = -1;
@@ -602,6 +618,25 @@ int fv_debug_read_activation(fv_ctx* c, int32_t which, int32_t n, float* out) {
             else { uint32_t u = (uint32_t)((const uint16_t*)buf.data())[i] << 16; memcpy(&v, &u, 4); }
             out[(size_t)t * F + f] = v;
         }
+    return FV_OK;
+}
+
+int fv_stream_read(fv_ctx* c, int32_t passes, float* gbytes_per_s) {
+    if (!c || !gbytes_per_s || passes < 1 || passes > 64) return FV_E_BAD_ARG;
+    // the tiled weights are the largest thing in the arena: read them (up to 4 GiB of them) from the start
+    size_t bytes = c->lay.off_embed < ((size_t)4 << 30) ? c->lay.off_embed : ((size_t)4 << 30);
+    bytes &= ~(size_t)(256 * 4 * 16 * 64 * 16 - 1);   // whole wavefront iterations for 256 workgroups
+    if (bytes == 0) return FV_E_BAD_ARG;
+    hipLaunchKernelGGL(k_stream_read, dim3(256), dim3(256), 0, c->stream, (const uint4*)c->arena, bytes / 16, c->at<uint4>(c->lay.off_zeros));
+    HIPCHK(hipEventRecord(c->ev0, c->stream));
+    for (int i = 0; i < passes; ++i)
+        hipLaunchKernelGGL(k_stream_read, dim3(256), dim3(256), 0, c->stream, (const uint4*)c->arena, bytes / 16, c->at<uint4>(c->lay.off_zeros));
+    HIPCHK(hipGetLastError());
+    HIPCHK(hipEventRecord(c->ev1, c->stream));
+    HIPCHK(hipStreamSynchronize(c->stream));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, c->ev0, c->ev1));
+    *gbytes_per_s = (float)((double)bytes * passes / (ms * 1e-3) / 1e9);
     return FV_OK;
 }
 
