@@ -104,3 +104,17 @@ def fill_tokens(seed: int, parent, vocab: int, root_token: int, planted=None, pl
         taken.add(t)
         tok[i] = t
     return tok
+
+
+def sibling_ranks(parent) -> np.ndarray:
+    """rank[i] = position of node i among the children of its parent, in index order (0 for the
+    root).  In a static decoding tree the child of rank r stands for the drafter's r-th most
+    likely token at that place (Appendix "Tree Structure")."""
+    n = len(parent)
+    rank = np.zeros(n, dtype=np.int32)
+    seen = {}
+    for i in range(1, n):
+        p = int(parent[i])
+        rank[i] = seen.get(p, 0)
+        seen[p] = rank[i] + 1
+    return rank

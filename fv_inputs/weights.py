@@ -95,3 +95,60 @@ def sub_model(shape: ModelShape, weights: dict, n_layers: int):
     keep = {k: v for k, v in weights.items()
             if not k.startswith("l") or k == "lm_head" or int(k.split(".")[0][1:]) < n_layers}
     return sub, keep
+
+
+# ----------------------------------------------------------------------------- drafter (SAR head)
+
+def drafter_tensor_ids(s: ModelShape):
+    """(name, shape) of the drafter's own tensors: two LSTM layers (fused input 2h -> h, then
+    h -> h; gate rows in the order input, forget, cell, output), one decoder layer of the target's
+    geometry.  Embedding and LM head are the target's (section "Framework and Computational
+    Process") and are not listed."""
+    h, qd, kvd = s.hidden, s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    return [
+        ("lstm0.w_ih", (4 * h, 2 * h)), ("lstm0.w_hh", (4 * h, h)), ("lstm0.b", (4 * h,)),
+        ("lstm1.w_ih", (4 * h, h)), ("lstm1.w_hh", (4 * h, h)), ("lstm1.b", (4 * h,)),
+        ("d.wq", (qd, h)), ("d.wk", (kvd, h)), ("d.wv", (kvd, h)), ("d.wo", (h, qd)),
+        ("d.wg", (s.ffn, h)), ("d.wu", (s.ffn, h)), ("d.wd", (h, s.ffn)),
+        ("d.g_attn", (h,)), ("d.g_mlp", (h,)),
+    ]
+
+
+def gen_drafter_weights(shape: ModelShape, seed: int = 0, gain_jitter: float = 0.0, bias_std: float = 0.1) -> dict:
+    """Random-init drafter tensors (the trained ones are not available): matrices N(0, 0.02) in the
+    shape's storage type, LSTM biases N(0, bias_std) in float32 (non-zero so that a dropped or
+    mis-indexed bias shows), gains 1 (+ jitter)."""
+    out = {}
+    for idx, (name, shp) in enumerate(drafter_tensor_ids(shape)):
+        if name.endswith(".b"):
+            rng = np.random.Generator(np.random.Philox(key=[seed, 4096 + idx]))
+            out[name] = (np.float32(bias_std) * rng.standard_normal(shp, dtype=np.float32)).astype(np.float32)
+            continue
+        if len(shp) == 1:   # gains: same recipe as the target's
+            rng = np.random.Generator(np.random.Philox(key=[seed, 4096 + idx]))
+            g = np.ones(shp, dtype=np.float32)
+            if gain_jitter:
+                g += np.float32(gain_jitter) * rng.standard_normal(shp, dtype=np.float32)
+            out[name] = g
+            continue
+        rng = np.random.Generator(np.random.Philox(key=[seed, 4096 + idx]))
+        rows, cols = shp
+        if shape.dtype == "f32":
+            w = rng.standard_normal(shp, dtype=np.float32)
+            w *= np.float32(STD)
+            out[name] = w
+        else:
+            arr = np.empty(shp, dtype=np.uint16)
+            step = max(1, (1 << 24) // cols)
+            for r0 in range(0, rows, step):
+                blk = rng.standard_normal((min(step, rows - r0), cols), dtype=np.float32)
+                blk *= np.float32(STD)
+                arr[r0:r0 + blk.shape[0]] = bf16_bits_from_f32(blk)
+            out[name] = arr
+    return out
+
+
+def gen_features(seed: int, n: int, hidden: int) -> np.ndarray:
+    """Stand-ins for target-model features (LM-head inputs after the final norm): N(0, 1) rows, float32."""
+    rng = np.random.Generator(np.random.Philox(key=[seed, 7020]))
+    return rng.standard_normal((n, hidden), dtype=np.float32)
