@@ -243,6 +243,82 @@ int fv_get_phase_times(fv_ctx* ctx, float* ms, int32_t* launches);
  * HIP events on the context's stream.  Always available. */
 int fv_last_step_ms(fv_ctx* ctx, float* ms);
 
+/* ============================================================================================
+ * Drafting phase: the SAR head of the paper (sections "Framework and Computational Process",
+ * "Coupled Sequential Glancing Distillation", "Custom-Designed Decoding Tree"; Appendix "Tree
+ * Structure").  The drafter is the target's embedding table, two LSTM layers that take the
+ * concatenation [feature of position j ; embedding of token j+1] (width 2*hidden) down to hidden,
+ * one decoder block of the target's geometry under the relaxed causal mask (a row sees its
+ * predecessors in the tree and every row of its own block of k rows), and the target's LM head.
+ * The row at position j predicts the feature of position j+k, so one pass over a block of k rows
+ * yields the distributions of the next k tokens; node i of the static tree at depth d takes the
+ * token of rank rank[i] (0 = most likely; ties: lower token id first) of the distribution of its
+ * depth.  The paper fixes neither dimensions nor wiring; the choices made here are listed in the
+ * design notes and implemented identically by the CPU oracle.
+ *
+ * State: the drafter keeps its own K/V cache and LSTM state over the committed pairs.  A phase is
+ *   fv_draft_commit (the pairs the target fixed since the last phase: n = accepted + 1 after a
+ *   verification step, the whole prompt after prefill), then at most one fv_draft_tree.
+ * Limits: k <= FV_DRAFT_MAX_K; rank < FV_DRAFT_MAX_M; at most 256 rows per phase (rows of the
+ *   commit's last piece + rows of all blocks); vocab <= 65536.
+ * The drafter shares the target context's stream, embedding table and LM head: the target context
+ * must outlive it and its weights must be set.  Calls are synchronous on return. */
+#define FV_DRAFT_MAX_K 8
+#define FV_DRAFT_MAX_M 32
+
+typedef struct fv_drafter fv_drafter;
+
+/* Host pointers; matrices row-major [out, in] in the target's dtype, biases and gains fp32.
+ * LSTM gate rows are ordered input, forget, cell, output; layer 0 is [4h, 2h] / [4h, h], layer 1
+ * [4h, h] / [4h, h]; one bias vector [4h] per layer. */
+typedef struct fv_drafter_host_weights {
+    const void* lstm_w_ih[2];
+    const void* lstm_w_hh[2];
+    const float* lstm_b[2];
+    const void *wq, *wk, *wv, *wo, *wg, *wu, *wd;   /* the decoder block, shapes as in fv_host_weights */
+    const float *g_attn, *g_mlp;
+} fv_drafter_host_weights;
+
+/* Bytes of device arena a drafter for a target of this shape needs.  Pure host arithmetic. */
+int fv_drafter_workspace_bytes(const fv_cfg* target_cfg, size_t* out_bytes);
+
+/* Create a drafter over a caller-owned device arena (256-byte aligned, zero-filled here). */
+int fv_drafter_create(fv_ctx* target, int32_t k, void* dev_arena, size_t arena_bytes, fv_drafter** out);
+void fv_drafter_destroy(fv_drafter* d);
+int fv_drafter_init_weights(fv_drafter* d, const fv_drafter_host_weights* host_weights);
+
+/* Forget all committed pairs (zero LSTM state, empty cache). */
+int fv_draft_reset(fv_drafter* d);
+
+/* Take in n >= 1 pairs the target has fixed: host_tokens[i] = token of position L+i+1,
+ * dev_features = DEVICE pointer to n rows of `hidden` fp32 (row i = the target's feature of
+ * position L+i, i.e. its LM-head input; for instance what fv_features_device_ptr gives after a
+ * verification step).  Rows are processed in sequence order under a causal mask; their K/V and
+ * the LSTM state are kept, L += n.  Opens a new phase. */
+int fv_draft_commit(fv_drafter* d, const int32_t* host_tokens, const float* dev_features, int32_t n);
+
+/* Fill a static tree with draft tokens.  parent / depth as for fv_verify_tree (node 0 = root =
+ * the token of the last committed pair, root_token); rank[i] = rank of node i among the
+ * candidates of its place.  tokens_out (host, n_nodes) receives the tree's tokens, ready for
+ * fv_verify_tree.  ceil(max depth / k) - 1 passes run (the first k levels come from the rows
+ * of the commit).  Needs at least k committed pairs and an open phase. */
+int fv_draft_tree(fv_drafter* d, const int32_t* parent_idx, const int32_t* depth, const int32_t* rank, int32_t n_nodes,
+                  int32_t root_token, int32_t* tokens_out);
+
+/* Read-back (tests): committed pairs, rows of the current phase, rows of its commit. */
+int fv_draft_get_state(fv_drafter* d, int32_t* committed, int32_t* phase_rows, int32_t* chain_rows);
+enum { FV_DRAFT_FEATURES = 0, FV_DRAFT_LOGITS = 1 };
+/* Predicted features [n, hidden] or logits [n, vocab] of phase rows row0.. (host, fp32). */
+int fv_draft_get_rows(fv_drafter* d, int32_t what, int32_t row0, int32_t n, float* out);
+/* Top lists [n, FV_DRAFT_MAX_M] of phase rows row0.. (host). */
+int fv_draft_get_top(fv_drafter* d, int32_t row0, int32_t n, int32_t* tokens_out);
+/* K and V of the drafter's cache slots (layout as fv_read_kv). */
+int fv_draft_read_kv(fv_drafter* d, int32_t slot0, int32_t n, float* k_out, float* v_out);
+/* Device time of the last fv_draft_commit / fv_draft_tree in milliseconds. */
+int fv_draft_last_ms(fv_drafter* d, float* ms);
+/* DEVICE address of the feature rows the last verification step exported (what fv_get_features copies). */
+int fv_features_device_ptr(fv_ctx* ctx, const float** dev_rows);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,11 @@ class fv_cfg(C.Structure):
                                          "dtype", "max_seq", "max_tree")] + [("rope_base", C.c_float), ("rms_eps", C.c_float)]
 
 
+class fv_drafter_host_weights(C.Structure):
+    _fields_ = [("lstm_w_ih", C.c_void_p * 2), ("lstm_w_hh", C.c_void_p * 2), ("lstm_b", C.c_void_p * 2)] + \
+               [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g_attn", "g_mlp")]
+
+
 class fv_host_weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("g_final", C.c_void_p)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g_attn", "g_mlp")]
@@ -76,6 +81,18 @@ def load_library():
         "fv_set_profiling": [vp, C.c_int32],
         "fv_get_phase_times": [vp, C.POINTER(C.c_float), i32p],
         "fv_last_step_ms": [vp, C.POINTER(C.c_float)],
+        "fv_drafter_workspace_bytes": [C.POINTER(fv_cfg), C.POINTER(C.c_size_t)],
+        "fv_drafter_create": [vp, C.c_int32, vp, C.c_size_t, C.POINTER(vp)],
+        "fv_drafter_init_weights": [vp, C.POINTER(fv_drafter_host_weights)],
+        "fv_draft_reset": [vp],
+        "fv_draft_commit": [vp, i32p, vp, C.c_int32],
+        "fv_draft_tree": [vp, i32p, i32p, i32p, C.c_int32, C.c_int32, i32p],
+        "fv_draft_get_state": [vp, i32p, i32p, i32p],
+        "fv_draft_get_rows": [vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float)],
+        "fv_draft_get_top": [vp, C.c_int32, C.c_int32, i32p],
+        "fv_draft_read_kv": [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float)],
+        "fv_draft_last_ms": [vp, C.POINTER(C.c_float)],
+        "fv_features_device_ptr": [vp, C.POINTER(vp)],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -83,6 +100,8 @@ def load_library():
         fn.restype = C.c_int
     lib.fv_destroy.argtypes = [vp]
     lib.fv_destroy.restype = None
+    lib.fv_drafter_destroy.argtypes = [vp]
+    lib.fv_drafter_destroy.restype = None
     _LIB = lib
     return lib
 
@@ -315,3 +334,125 @@ class FalconVerifier:
         v = C.c_float()
         self._chk(self.lib.fv_last_step_ms(self.ctx, C.byref(v)), "fv_last_step_ms")
         return v.value
+
+
+DRAFT_MAX_M = 32
+
+
+class FalconDrafter:
+    """The drafting phase next to a FalconVerifier (whose stream, embedding table and LM head it uses):
+    owns its torch arena and the fv_drafter."""
+
+    def __init__(self, target: FalconVerifier, k: int):
+        import torch
+        self.lib, self.target, self.k = target.lib, target, int(k)
+        out = C.c_size_t(0)
+        rc = self.lib.fv_drafter_workspace_bytes(C.byref(target.cfg), C.byref(out))
+        if rc:
+            raise FvError(rc, "fv_drafter_workspace_bytes")
+        self.bytes = out.value
+        self.arena = torch.empty(self.bytes + 256, dtype=torch.uint8, device=target.device)
+        self._ptr = (self.arena.data_ptr() + 255) // 256 * 256
+        h = C.c_void_p()
+        rc = self.lib.fv_drafter_create(target.ctx, self.k, C.c_void_p(self._ptr), C.c_size_t(self.bytes), C.byref(h))
+        if rc:
+            raise FvError(rc, "fv_drafter_create")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.fv_drafter_destroy(self.h)
+            self.h = None
+        self.arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _chk(self, rc, where):
+        if rc:
+            raise FvError(rc, where)
+
+    def init_weights(self, weights: dict):
+        """weights: the drafter's own tensors by name (lstm{0,1}.{w_ih,w_hh,b}, d.{wq,..,wd,g_attn,g_mlp})."""
+        want = np.uint16 if self.target.shape.dtype == "bf16" else np.float32
+        keep = []
+
+        def ptr(name, dt):
+            a = weights[name]
+            if a.dtype != dt:
+                raise TypeError(f"{name}: expected {dt}, got {a.dtype}")
+            a = np.ascontiguousarray(a)
+            keep.append(a)
+            return a.ctypes.data
+
+        hw = fv_drafter_host_weights(
+            (C.c_void_p * 2)(ptr("lstm0.w_ih", want), ptr("lstm1.w_ih", want)),
+            (C.c_void_p * 2)(ptr("lstm0.w_hh", want), ptr("lstm1.w_hh", want)),
+            (C.c_void_p * 2)(ptr("lstm0.b", np.float32), ptr("lstm1.b", np.float32)),
+            *[ptr(f"d.{n}", want) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")],
+            ptr("d.g_attn", np.float32), ptr("d.g_mlp", np.float32))
+        self._chk(self.lib.fv_drafter_init_weights(self.h, C.byref(hw)), "fv_drafter_init_weights")
+
+    def reset(self):
+        self._chk(self.lib.fv_draft_reset(self.h), "fv_draft_reset")
+
+    def commit(self, tokens, features):
+        """features: a torch float32 CUDA tensor [n, hidden] (or a raw device address) of the target's features."""
+        t, tp = _i32(tokens)
+        if hasattr(features, "data_ptr"):
+            if features.dtype.__str__() != "torch.float32" or not features.is_contiguous() or features.shape[0] < len(t):
+                raise TypeError("features: contiguous float32 [n, hidden] on the GPU")
+            addr = features.data_ptr()
+        else:
+            addr = int(features)
+        self._chk(self.lib.fv_draft_commit(self.h, tp, C.c_void_p(addr), len(t)), "fv_draft_commit")
+
+    def draft_tree(self, parent, depth, rank, root_token: int):
+        p, pp = _i32(parent)
+        d, dp = _i32(depth)
+        r, rp = _i32(rank)
+        out = np.zeros(len(p), dtype=np.int32)
+        self._chk(self.lib.fv_draft_tree(self.h, pp, dp, rp, len(p), int(root_token), out.ctypes.data_as(C.POINTER(C.c_int32))),
+                  "fv_draft_tree")
+        return out
+
+    def state(self):
+        a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+        self._chk(self.lib.fv_draft_get_state(self.h, C.byref(a), C.byref(b), C.byref(c)), "fv_draft_get_state")
+        return a.value, b.value, c.value
+
+    def rows(self, what: str, row0: int, n: int):
+        width = self.target.shape.hidden if what == "features" else self.target.shape.vocab
+        out = np.zeros((n, width), dtype=np.float32)
+        self._chk(self.lib.fv_draft_get_rows(self.h, 0 if what == "features" else 1, row0, n,
+                                             out.ctypes.data_as(C.POINTER(C.c_float))), "fv_draft_get_rows")
+        return out
+
+    def top(self, row0: int, n: int):
+        out = np.zeros((n, DRAFT_MAX_M), dtype=np.int32)
+        self._chk(self.lib.fv_draft_get_top(self.h, row0, n, out.ctypes.data_as(C.POINTER(C.c_int32))), "fv_draft_get_top")
+        return out
+
+    def read_kv(self, slot0: int, n: int):
+        s = self.target.shape
+        k = np.zeros((n, s.n_kv_heads, s.head_dim), dtype=np.float32)
+        v = np.zeros_like(k)
+        self._chk(self.lib.fv_draft_read_kv(self.h, slot0, n, k.ctypes.data_as(C.POINTER(C.c_float)),
+                                            v.ctypes.data_as(C.POINTER(C.c_float))), "fv_draft_read_kv")
+        return k, v
+
+    def last_ms(self) -> float:
+        ms = C.c_float(0)
+        self._chk(self.lib.fv_draft_last_ms(self.h, C.byref(ms)), "fv_draft_last_ms")
+        return ms.value
+
+
+def features_device_ptr(target: FalconVerifier) -> int:
+    out = C.c_void_p()
+    rc = target.lib.fv_features_device_ptr(target.ctx, C.byref(out))
+    if rc:
+        raise FvError(rc, "fv_features_device_ptr")
+    return out.value

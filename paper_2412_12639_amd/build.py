@@ -16,7 +16,7 @@ DEPS = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC)) + \
     [os.path.join(os.path.dirname(HERE), "include", "falcon_verify.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
-UNITS = [("falcon_verify", "falcon_verify.hip", [])] + \
+UNITS = [("falcon_verify", "falcon_verify.hip", []), ("fv_draft", "fv_draft.hip", [])] + \
     [(f"fv_step_{el.lower()}_d{d}", "fv_step.hip", [f"-DFV_INST_EL={el}", f"-DFV_INST_D={d}"])
      for el in ("BF16", "F32") for d in (128, 64)]
 

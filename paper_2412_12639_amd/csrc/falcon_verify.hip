@@ -3,6 +3,7 @@
 // of a step lives in fv_step.hip, compiled once per (element type, head size) pair.
 #include "fv_host.hpp"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -60,8 +61,6 @@ static int static_scratch_ptr(char** out) {
     return FV_OK;
 }
 
-namespace {
-
 int check_cfg(const fv_cfg* c) {
     if (!c) return FV_E_BAD_ARG;
     if (c->dtype != FV_F32 && c->dtype != FV_BF16) return FV_E_BAD_ARG;
@@ -78,7 +77,7 @@ int check_cfg(const fv_cfg* c) {
 
 // R strips per row group; stage_frags fragments (of 2E columns) per K step of the split (the
 // tiled buffer itself is always padded to whole 8-fragment batches)
-void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R, int stage_frags = FV_FRAGS) {
+static void plan_gemm(GemmPlan& p, int n_strips, int K, int E, int n_wg, int R = FV_R, int stage_frags = FV_FRAGS) {
     const int KB = 16 * E;
     p.K = K;
     p.Kpad = (int)rup(K, KB);
@@ -122,36 +121,48 @@ int build_split_tables(const GemmPlan& p, std::vector<int>& tab) {
     return n_fix;
 }
 
-void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
+// The three forms of one matrix: shared-activation kernel (row groups of FV_R strips), direct kernel
+// (one strip per wavefront) and its paired form (two strips per wavefront, half-batch stages).
+void plan_gemm_forms(GemmPlan& gm, GemmPlan& gd, GemmPlan& gp, bool& paired_ok, int n_strips, int K, int E, int n_wg) {
+    plan_gemm(gm, n_strips, K, E, n_wg);
+    plan_gemm(gd, gm.n_strips, gm.K, E, n_wg, 1);
+    plan_gemm(gp, gm.n_strips, gm.K, E, n_wg, 2, FV_FRAGS / 2);
+    // a full K range must give each of the four wavefronts at least three stages, so that no
+    // wavefront meets more than two segment ends within one round of three stages
+    paired_ok = gp.NB >= 12;
+    // Whole row groups per workgroup need no partial-tile exchange at all, but the group counts
+    // differ by one between workgroups: worth it only when that idles little of the chip (the
+    // LM head: 500 groups of 64 rows over 256 workgroups).  (FV_GEMM_ALIGN=0 / 1 forces it off / on.)
+    const char* al = getenv("FV_GEMM_ALIGN");
+    for (GemmPlan* q : {&gd, &gp}) {
+        if (q->NG < q->G) continue;
+        const int per = (q->NG + q->G - 1) / q->G;
+        const double idle = (double)((long long)per * q->G - q->NG) / (double)q->NG;
+        q->aligned = al ? (!strcmp(al, "1") ? 1 : 0) : (idle <= 0.10 ? 1 : 0);
+    }
+    for (GemmPlan* q : {&gd, &gp})
+        if (q->aligned) q->segmax = (q->NG + q->G - 1) / q->G + 1;
+}
+
+// bytes of partial tiles the three forms of one matrix can need at up to T rows (T a multiple of 32)
+size_t plan_part_bytes(const GemmPlan& gm, const GemmPlan& gd, const GemmPlan& gp, size_t T) {
+    const size_t b = (size_t)gm.G * gm.segmax * FV_R * (T / 32) * 4096;
+    const size_t bd = (size_t)gd.G * gd.segmax * 2 * 4096;
+    const size_t bp = (size_t)gp.G * gp.segmax * 4 * 4096;
+    return std::max(b, std::max(bd, bp));
+}
+
+size_t plan_table_bytes(const GemmPlan& p) { return (size_t)(2 * p.G + 1 + 6 * p.NG) * 4 + 16; }
+
+void make_layout(const fv_cfg& c, int n_wg, Layout& L, bool own_head, size_t min_stage_elems) {
     L.E = c.dtype == FV_BF16 ? 8 : 4;
     L.ESZ = c.dtype == FV_BF16 ? 2 : 4;
     L.Tpm = pad_tokens(c.max_tree);
     L.S_pad = (int)rup(c.max_seq, 32);
     const int d = c.head_dim, qd = c.n_q_heads * d, kvd = c.n_kv_heads * d;
-    plan_gemm(L.gm[GM_QKV], (qd + 2 * kvd) / 32, c.hidden, L.E, n_wg);
-    plan_gemm(L.gm[GM_O], c.hidden / 32, qd, L.E, n_wg);
-    plan_gemm(L.gm[GM_GU], c.ffn / 16, c.hidden, L.E, n_wg);
-    plan_gemm(L.gm[GM_DN], c.hidden / 32, c.ffn, L.E, n_wg);
-    plan_gemm(L.gm[GM_LM], (c.vocab + 31) / 32, c.hidden, L.E, n_wg);
-    for (int i = 0; i < GM_COUNT; ++i) {
-        plan_gemm(L.gd[i], L.gm[i].n_strips, L.gm[i].K, L.E, n_wg, 1);
-        plan_gemm(L.gp[i], L.gm[i].n_strips, L.gm[i].K, L.E, n_wg, 2, FV_FRAGS / 2);
-        // a full K range must give each of the four wavefronts at least three stages, so that no
-        // wavefront meets more than two segment ends within one round of three stages
-        L.paired_ok[i] = L.gp[i].NB >= 12;
-        // Whole row groups per workgroup need no partial-tile exchange at all, but the group counts
-        // differ by one between workgroups: worth it only when that idles little of the chip (the
-        // LM head: 500 groups of 64 rows over 256 workgroups).  (FV_GEMM_ALIGN=0 / 1 forces it off / on.)
-        const char* al = getenv("FV_GEMM_ALIGN");
-        for (GemmPlan* q : {&L.gd[i], &L.gp[i]}) {
-            if (q->NG < q->G) continue;
-            const int per = (q->NG + q->G - 1) / q->G;
-            const double idle = (double)((long long)per * q->G - q->NG) / (double)q->NG;
-            q->aligned = al ? (!strcmp(al, "1") ? 1 : 0) : (idle <= 0.10 ? 1 : 0);
-        }
-        for (GemmPlan* q : {&L.gd[i], &L.gp[i]})
-            if (q->aligned) q->segmax = (q->NG + q->G - 1) / q->G + 1;
-    }
+    const int ns[GM_COUNT] = {(qd + 2 * kvd) / 32, c.hidden / 32, c.ffn / 16, c.hidden / 32, (c.vocab + 31) / 32};
+    const int ks[GM_COUNT] = {c.hidden, qd, c.hidden, c.ffn, c.hidden};
+    for (int i = 0; i < GM_COUNT; ++i) plan_gemm_forms(L.gm[i], L.gd[i], L.gp[i], L.paired_ok[i], ns[i], ks[i], L.E, n_wg);
     L.Vpad = L.gm[GM_LM].n_strips * 32;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o = rup(o + bytes, 256); return r; };
@@ -159,8 +170,8 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     for (int i = 0; i < 4; ++i) { L.off_w[i] = lw; lw = rup(lw + L.gm[i].tiled_bytes, 256); }
     L.layer_w_bytes = lw;
     L.off_layers = take(lw * c.n_layers);
-    L.off_lm = take(L.gm[GM_LM].tiled_bytes);
-    L.off_embed = take((size_t)c.vocab * c.hidden * L.ESZ);
+    L.off_lm = take(own_head ? L.gm[GM_LM].tiled_bytes : 0);   // a drafter uses the target's head and embedding
+    L.off_embed = take(own_head ? (size_t)c.vocab * c.hidden * L.ESZ : 0);
     L.off_gains = take((size_t)(2 * c.n_layers + 1) * c.hidden * 4);
     L.kv_layer_bytes = (size_t)c.n_kv_heads * L.S_pad * d * L.ESZ;
     L.off_k = take(L.kv_layer_bytes * c.n_layers);
@@ -176,23 +187,16 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     L.off_ssq = take((size_t)(c.hidden / 32) * T * 4);
     L.off_rinv = take(T * 4);
     size_t pb = 0;
-    for (int i = 0; i < GM_COUNT; ++i) {
-        const size_t b = (size_t)L.gm[i].G * L.gm[i].segmax * FV_R * (T / 32) * 4096;
-        if (b > pb) pb = b;
-        const size_t bd = (size_t)L.gd[i].G * L.gd[i].segmax * 2 * 4096;
-        if (bd > pb) pb = bd;
-        const size_t bp = (size_t)L.gp[i].G * L.gp[i].segmax * 4 * 4096;
-        if (bp > pb) pb = bp;
-    }
+    for (int i = 0; i < GM_COUNT; ++i) pb = std::max(pb, plan_part_bytes(L.gm[i], L.gd[i], L.gp[i], T));
     L.part_bytes = pb;
     L.off_part = take(pb);
     int ngmax = 0;
     for (int i = 0; i < GM_COUNT; ++i) if (L.gm[i].n_strips_pad > ngmax) ngmax = L.gm[i].n_strips_pad;
     L.off_tickets = take((size_t)ngmax * 4);
     for (int i = 0; i < GM_COUNT; ++i) {
-        L.gm[i].off_tab = take((size_t)(2 * L.gm[i].G + 1 + 6 * L.gm[i].NG) * 4 + 16);
-        L.gd[i].off_tab = take((size_t)(2 * L.gd[i].G + 1 + 6 * L.gd[i].NG) * 4 + 16);
-        L.gp[i].off_tab = take((size_t)(2 * L.gp[i].G + 1 + 6 * L.gp[i].NG) * 4 + 16);
+        L.gm[i].off_tab = take(plan_table_bytes(L.gm[i]));
+        L.gd[i].off_tab = take(plan_table_bytes(L.gd[i]));
+        L.gp[i].off_tab = take(plan_table_bytes(L.gp[i]));
     }
     L.off_zeros = take(32768);   // never written after the arena is cleared
     L.off_stepin = take(3 * FV_MAX_TREE * 4);
@@ -208,7 +212,8 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     size_t st = (size_t)(qd + 2 * kvd) * c.hidden;
     const size_t cands[4] = {(size_t)c.hidden * qd, (size_t)2 * c.ffn * c.hidden, (size_t)c.hidden * c.ffn,
                              (size_t)c.vocab * c.hidden};
-    for (size_t v : cands) if (v > st) st = v;
+    for (size_t v : cands) if (v > st && (own_head || v != cands[3])) st = v;
+    if (min_stage_elems > st) st = min_stage_elems;
     L.stage_bytes = st * L.ESZ;
     L.off_stage = take(L.stage_bytes);
     // attention key-split partials: at most 8 parts per (head, node block) item, items for 256 rows
@@ -216,6 +221,8 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L) {
     L.off_atick = take((size_t)c.n_q_heads * 8 * 4);
     L.total = o;
 }
+
+namespace {
 
 int validate_tree(const fv_cfg& c, const int32_t* tok, const int32_t* parent, const int32_t* depth, int n,
                   int pending, int cur_len, bool check_root) {
@@ -234,10 +241,6 @@ int validate_tree(const fv_cfg& c, const int32_t* tok, const int32_t* parent, co
     return FV_OK;
 }
 
-}  // namespace
-
-namespace {
-
 template <typename EL>
 int run_step_d(fv_ctx* c, int T, StepMode mode) {
     return c->cfg.head_dim == 128 ? run_step<EL, 128>(c, T, mode) : run_step<EL, 64>(c, T, mode);
@@ -252,29 +255,57 @@ int set_gemm_attrs(int head_dim) {
 }
 
 template <typename EL>
-int init_weights_t(fv_ctx* c, const fv_host_weights* w) {
+int init_layer_t(fv_ctx* c, int l, const void* wq, const void* wk, const void* wv, const void* wo, const void* wg, const void* wu,
+                 const void* wd, const float* g_attn, const float* g_mlp) {
     const fv_cfg& cf = c->cfg;
     const Layout& ly = c->lay;
     const size_t h = cf.hidden, qd = (size_t)cf.n_q_heads * cf.head_dim, kvd = (size_t)cf.n_kv_heads * cf.head_dim, F = cf.ffn;
+    if (!wq || !wk || !wv || !wo || !wg || !wu || !wd || !g_attn || !g_mlp) return FV_E_BAD_ARG;
+    int rc = tile_upload<EL>(c, TILE_QKV, ly.gm[GM_QKV], c->layer_w(l, 0), wq, qd * h, wk, kvd * h, wv, kvd * h, 0);
+    if (rc) return rc;
+    rc = tile_upload<EL>(c, TILE_NAT, ly.gm[GM_O], c->layer_w(l, 1), wo, h * qd, nullptr, 0, nullptr, 0, (int)h);
+    if (rc) return rc;
+    rc = tile_upload<EL>(c, TILE_GU, ly.gm[GM_GU], c->layer_w(l, 2), wg, F * h, wu, F * h, nullptr, 0, 0);
+    if (rc) return rc;
+    rc = tile_upload<EL>(c, TILE_NAT, ly.gm[GM_DN], c->layer_w(l, 3), wd, h * F, nullptr, 0, nullptr, 0, (int)h);
+    if (rc) return rc;
+    HIPCHK(hipMemcpy(c->gain(2 * l), g_attn, h * 4, hipMemcpyHostToDevice));
+    HIPCHK(hipMemcpy(c->gain(2 * l + 1), g_mlp, h * 4, hipMemcpyHostToDevice));
+    return FV_OK;
+}
+
+template <typename EL>
+int init_weights_t(fv_ctx* c, const fv_host_weights* w) {
+    const fv_cfg& cf = c->cfg;
+    const Layout& ly = c->lay;
+    const size_t h = cf.hidden;
     for (int l = 0; l < cf.n_layers; ++l) {
-        if (!w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->wg[l] || !w->wu[l] || !w->wd[l] || !w->g_attn[l] || !w->g_mlp[l])
-            return FV_E_BAD_ARG;
-        int rc = tile_upload<EL>(c, TILE_QKV, ly.gm[GM_QKV], c->layer_w(l, 0), w->wq[l], qd * h, w->wk[l], kvd * h, w->wv[l], kvd * h, 0);
+        int rc = init_layer_t<EL>(c, l, w->wq[l], w->wk[l], w->wv[l], w->wo[l], w->wg[l], w->wu[l], w->wd[l], w->g_attn[l], w->g_mlp[l]);
         if (rc) return rc;
-        rc = tile_upload<EL>(c, TILE_NAT, ly.gm[GM_O], c->layer_w(l, 1), w->wo[l], h * qd, nullptr, 0, nullptr, 0, (int)h);
-        if (rc) return rc;
-        rc = tile_upload<EL>(c, TILE_GU, ly.gm[GM_GU], c->layer_w(l, 2), w->wg[l], F * h, w->wu[l], F * h, nullptr, 0, 0);
-        if (rc) return rc;
-        rc = tile_upload<EL>(c, TILE_NAT, ly.gm[GM_DN], c->layer_w(l, 3), w->wd[l], h * F, nullptr, 0, nullptr, 0, (int)h);
-        if (rc) return rc;
-        HIPCHK(hipMemcpy(c->gain(2 * l), w->g_attn[l], h * 4, hipMemcpyHostToDevice));
-        HIPCHK(hipMemcpy(c->gain(2 * l + 1), w->g_mlp[l], h * 4, hipMemcpyHostToDevice));
     }
     int rc = tile_upload<EL>(c, TILE_NAT, ly.gm[GM_LM], c->arena + ly.off_lm, w->lm_head, (size_t)cf.vocab * h, nullptr, 0, nullptr, 0, cf.vocab);
     if (rc) return rc;
     HIPCHK(hipMemcpy(c->gain(2 * cf.n_layers), w->g_final, h * 4, hipMemcpyHostToDevice));
     HIPCHK(hipMemcpy(c->arena + ly.off_embed, w->embed, (size_t)cf.vocab * h * ly.ESZ, hipMemcpyHostToDevice));
     return FV_OK;
+}
+
+}  // namespace
+
+int init_layer_weights(fv_ctx* c, int l, const void* wq, const void* wk, const void* wv, const void* wo, const void* wg,
+                       const void* wu, const void* wd, const float* g_attn, const float* g_mlp) {
+    return c->cfg.dtype == FV_BF16 ? init_layer_t<BF16>(c, l, wq, wk, wv, wo, wg, wu, wd, g_attn, g_mlp)
+                                   : init_layer_t<F32>(c, l, wq, wk, wv, wo, wg, wu, wd, g_attn, g_mlp);
+}
+
+int upload_tiled(fv_ctx* c, const GemmPlan& p, char* out, const void* host, size_t n_elems, int N) {
+    return c->cfg.dtype == FV_BF16 ? tile_upload<BF16>(c, TILE_NAT, p, out, host, n_elems, nullptr, 0, nullptr, 0, N)
+                                   : tile_upload<F32>(c, TILE_NAT, p, out, host, n_elems, nullptr, 0, nullptr, 0, N);
+}
+
+int gemm_kind_from_env() {
+    const char* e = getenv("FV_GEMM");
+    return !e ? GEMM_PAIRED : !strcmp(e, "shared") ? GEMM_SHARED : !strcmp(e, "direct") ? GEMM_DIRECT : GEMM_PAIRED;
 }
 
 int n_workgroups() {
@@ -287,8 +318,6 @@ int n_workgroups() {
     if (n > 4096) n = 4096;
     return n;
 }
-
-}  // namespace
 
 extern "C" {
 
@@ -315,7 +344,7 @@ int fv_workspace_bytes(const fv_cfg* cfg, size_t* out_bytes) {
     int rc = check_cfg(cfg);
     if (rc) return rc;
     Layout L;
-    make_layout(*cfg, n_workgroups(), L);
+    make_layout(*cfg, n_workgroups(), L, true, 0);
     *out_bytes = L.total;
     return FV_OK;
 }
@@ -328,6 +357,13 @@ int fv_validate_tree(const fv_cfg* cfg, const int32_t* tok, const int32_t* paren
 }
 
 int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_stream, fv_ctx** out) {
+    return fv_create_ex(cfg, dev_arena, arena_bytes, hip_stream, true, 0, out);
+}
+
+}  // extern "C"
+
+int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_stream, bool own_head, size_t min_stage_elems,
+                 fv_ctx** out) {
     if (!out) return FV_E_BAD_ARG;
     *out = nullptr;
     int rc = check_cfg(cfg);
@@ -336,15 +372,14 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     fv_ctx* c = new (std::nothrow) fv_ctx();
     if (!c) return FV_E_BAD_ARG;
     c->cfg = *cfg;
-    make_layout(*cfg, n_workgroups(), c->lay);
+    make_layout(*cfg, n_workgroups(), c->lay, own_head, min_stage_elems);
     if (arena_bytes < c->lay.total) { delete c; return FV_E_BAD_ARG; }
     c->arena = (char*)dev_arena;
     c->stream = (hipStream_t)hip_stream;
     {   // GEMM kernel up to 64 tokens.  Default: the paired form wherever its staging slots suffice.
         // FV_GEMM = direct | paired | shared forces one kind; FV_GEMM_PAIRED_SET = bit mask over
         // (QKV, O, gate/up, down, head) restricts the paired form to those matrices (tuning aid).
-        const char* e = getenv("FV_GEMM");
-        const int kind = !e ? GEMM_PAIRED : !strcmp(e, "shared") ? GEMM_SHARED : !strcmp(e, "direct") ? GEMM_DIRECT : GEMM_PAIRED;
+        const int kind = gemm_kind_from_env();
         const char* m = getenv("FV_GEMM_PAIRED_SET");
         const int mask = m ? atoi(m) : 31;
         for (int i = 0; i < GM_COUNT; ++i) {
@@ -409,6 +444,8 @@ int fv_create(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_
     *out = c;
     return FV_OK;
 }
+
+extern "C" {
 
 void fv_destroy(fv_ctx* c) {
     if (!c) return;

@@ -113,6 +113,79 @@ struct fv_ctx {
 };
 
 
+// ============================================================================ drafting phase
+#define FV_DRAFT_STATE_COMMITTED FV_MAX_TREE        // state row of the last committed pair
+#define FV_DRAFT_OUT_ROWS (FV_MAX_TREE + FV_DRAFT_KMAX)   // output rows: phase rows + history slots
+#define FV_DRAFT_TABLES 11                          // int32 [256] tables of a phase (DraftTables)
+
+struct GemmForms {
+    GemmPlan gm, gd, gp;
+    bool paired_ok = false;
+    const GemmPlan& pick(int kind) const { return kind == GEMM_DIRECT ? gd : kind == GEMM_PAIRED ? gp : gm; }
+};
+
+struct DraftLayout {
+    GemmForms ih0, hh;                    // [4h x 2h] and [4h x h] (the latter serves lstm0.w_hh, lstm1.w_ih, lstm1.w_hh)
+    size_t off_core = 0, core_bytes = 0;  // the decoder block: a one-layer context without head and embedding
+    size_t off_w[4] = {0, 0, 0, 0};       // tiled lstm0.w_ih, lstm0.w_hh, lstm1.w_ih, lstm1.w_hh
+    size_t off_bias = 0, off_ones = 0;
+    size_t off_xz = 0, off_xh = 0, off_xprev = 0, off_gin = 0, off_grec = 0;
+    size_t off_state = 0, state_layer_bytes = 0;
+    size_t off_fout = 0, off_top_tok = 0, off_top_val = 0, off_logits = 0, off_node_tok = 0, off_tables = 0, off_bad = 0;
+    size_t off_part = 0, part_bytes = 0, off_tickets = 0, ticket_bytes = 0;
+    size_t total = 0;
+};
+
+// one pass of the drafter over phase rows r0 .. r0+n-1
+struct DraftPass {
+    int r0 = 0, n = 0;
+    int l0 = 0;                      // first entry of this pass in lvl_rows
+    std::vector<int> lvl_n;          // rows per LSTM level
+    int e0 = 0, n_exp = 0;           // tree nodes this pass generates: exp_list[e0 .. e0+n_exp)
+    const float* ext = nullptr;      // external features (device), rows addressed by feat_src = -1 - e
+};
+
+struct fv_drafter {
+    fv_ctx* target = nullptr;
+    fv_ctx* core = nullptr;
+    DraftLayout lay;
+    StepScratch scr;              // partial tiles and tickets large enough for every matrix of the drafter
+    char* arena = nullptr;
+    int k = 0;
+    bool weights_set = false;
+    int L = 0;                    // committed pairs whose K/V are in the cache
+    int L0 = 0;                   // cache slot of phase row 0
+    int n_chain = 0;              // rows of the current phase's chain (0: no phase open)
+    int n_rows = 0;               // phase rows so far
+    int last_Tp = 0;
+    int32_t* h_tab = nullptr;     // pinned [FV_DRAFT_TABLES][256]
+    int32_t* h_out = nullptr;     // pinned [256] node tokens + [1] error flag
+    float last_ms = 0.f;
+    int kind_ih0 = 0, kind_hh = 0;   // GemmKind up to 64 rows
+
+    template <typename T> T* at(size_t off) const { return (T*)(arena + off); }
+    float* state(int layer) const { return (float*)(arena + lay.off_state + (size_t)layer * lay.state_layer_bytes); }
+    int32_t* tab(int which) const { return (int32_t*)(arena + lay.off_tables) + (size_t)which * FV_MAX_TREE; }
+};
+
+// ---- defined in falcon_verify.hip
+int check_cfg(const fv_cfg* c);
+int n_workgroups();
+int gemm_kind_from_env();   // FV_GEMM = paired (default) | direct | shared
+void plan_gemm_forms(GemmPlan& gm, GemmPlan& gd, GemmPlan& gp, bool& paired_ok, int n_strips, int K, int E, int n_wg);
+size_t plan_part_bytes(const GemmPlan& gm, const GemmPlan& gd, const GemmPlan& gp, size_t T);
+size_t plan_table_bytes(const GemmPlan& p);
+int build_split_tables(const GemmPlan& p, std::vector<int>& tab);
+// own_head = false: no LM head and no embedding table in the arena (a drafter uses the target's);
+// min_stage_elems: the upload staging area holds at least that many elements
+void make_layout(const fv_cfg& c, int n_wg, Layout& L, bool own_head, size_t min_stage_elems);
+int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* hip_stream, bool own_head, size_t min_stage_elems,
+                 fv_ctx** out);
+int init_layer_weights(fv_ctx* c, int l, const void* wq, const void* wk, const void* wv, const void* wo, const void* wg,
+                       const void* wu, const void* wd, const float* g_attn, const float* g_mlp);
+// upload one row-major [N][K] matrix (p.K = K) and re-tile it for the plan's kernels
+int upload_tiled(fv_ctx* c, const GemmPlan& p, char* out, const void* host, size_t n_elems, int N);
+
 // ---- defined in fv_step.hip, instantiated once per (EL, D) pair
 // One pass of the decoder over T new rows whose tokens/parent/depth are in c->h_in.
 template <typename EL, int D> int run_step(fv_ctx* c, int T, StepMode mode);
@@ -120,6 +193,8 @@ template <typename EL, int D> int run_step(fv_ctx* c, int T, StepMode mode);
 template <typename EL, int D> int set_gemm_attrs_d();
 template <typename EL, int D> int read_kv_t(fv_ctx* c, int layer, int slot0, int n, float* k_out, float* v_out);
 // upload one weight tensor (up to three host pieces) and re-tile it on the device (independent of D)
+// one pass of the drafter (defined in fv_draft_step.hpp, part of the fv_step.hip units)
+template <typename EL, int D> int run_draft_pass(fv_drafter* d, const DraftPass& ps);
 template <typename EL>
 int tile_upload(fv_ctx* c, int kind, const GemmPlan& p, char* out, const void* h0, size_t n0, const void* h1, size_t n1,
                 const void* h2, size_t n2, int N);

@@ -736,6 +736,8 @@ struct AttnArgs {
     void* out;               // vector-major [Hq*D/E][Tp]
     const uint64_t* mask;    // [Tp][4]
     int Tp, T, L, Hq, Hkv, S_pad;
+    int TK;                  // step rows whose keys exist, slots L .. L+TK-1 (= T in a verification step; a drafting pass also sees
+                             // the rows of the phase's earlier passes); the masks have no bits at or above TK
     float scale;
     // key split: every (head, node block) item is shared by `ks` workgroups, each taking a
     // contiguous run of 32-key blocks; their (max, sum, unnormalised output) triples meet in
@@ -785,7 +787,7 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, int item, int part,
         for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float m_run = -1e30f, l_run = 0.f;
 
-    const int n_keys = a.L + a.T;
+    const int n_keys = a.L + a.TK;
     const int nkb = (n_keys + 31) >> 5;
     const int kb_lo = nkb * part / a.ks, kb_hi = nkb * (part + 1) / a.ks;   // this workgroup's key blocks
     const int lidx = tl * 2 + g;   // position of this lane's 16 bytes inside a 1 KiB tile

@@ -160,7 +160,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             AttnArgs aa;
             aa.q = c->at<uint4>(ly.off_q); aa.q_lo = c->at<uint4>(ly.off_qlo); aa.kc = (const uint4*)c->kc(l); aa.vc = (const uint4*)c->vc(l);
             aa.out = c->at<void>(ly.off_attn); aa.mask = c->at<uint64_t>(ly.off_mask);
-            aa.Tp = Tp; aa.T = T; aa.L = L; aa.Hq = cf.n_q_heads; aa.Hkv = cf.n_kv_heads; aa.S_pad = ly.S_pad;
+            aa.Tp = Tp; aa.T = T; aa.TK = T; aa.L = L; aa.Hq = cf.n_q_heads; aa.Hkv = cf.n_kv_heads; aa.S_pad = ly.S_pad;
             aa.scale = 1.f / std::sqrt((float)D);
             aa.ks = attn_key_split(cf.n_q_heads * (Tp / 32), L + T, 256);
             aa.part = c->scr->apart; aa.tickets = c->scr->atick;
@@ -299,7 +299,10 @@ int read_kv_t(fv_ctx* c, int layer, int slot0, int n, float* k_out, float* v_out
 }
 
 
+#include "fv_draft_step.hpp"
+
 template int run_step<FV_INST_EL, FV_INST_D>(fv_ctx*, int, StepMode);
+template int run_draft_pass<FV_INST_EL, FV_INST_D>(fv_drafter*, const DraftPass&);
 template int set_gemm_attrs_d<FV_INST_EL, FV_INST_D>();
 template int read_kv_t<FV_INST_EL, FV_INST_D>(fv_ctx*, int, int, int, float*, float*);
 #if FV_INST_D == 128

@@ -6,6 +6,9 @@
 #define FV_R 4            // strips (wavefronts) per GEMM workgroup
 #define FV_FRAGS 8        // weight frags per K batch
 
+#define FV_DRAFT_KMAX 8   // largest k of the semi-autoregressive drafter
+#define FV_DRAFT_MMAX 32  // longest top list per drafter row
+
 #define FV_SCAN_NONFINITE (-2)   // FvResult.accepted_len when some node's logits hold a NaN or an infinity
 
 // Result of the longest-accepted-path scan, written by the device and copied to the host.
