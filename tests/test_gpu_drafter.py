@@ -44,16 +44,31 @@ def _rel(a, b):
     return float(np.max(np.abs(a - b)) / max(1e-30, np.max(np.abs(b))))
 
 
+def _tol_of_pass(tol, p):
+    """Rows of pass p (the commit's rows are pass 0) are computed from the outputs of pass p - 1: its predicted
+    features and its LSTM states, two channels that carry the same rounding errors, so the errors of successive
+    passes add up rather than average out (measured at the 7B width: 0.5e-2 of the largest logit per pass).
+    The 2e-2 bar is kept for the commit's rows and the first tree pass and widened by 1e-2 per further pass
+    (bf16 builds only; fp32 builds keep their flat tolerance)."""
+    return tol if tol < 1e-3 else tol * max(1.0, (p + 1) / 2)
+
+
 def _check_phase(s, dr, orc, n_chain, tokens_dev, parent, depth, rank, tol):
     """Rows of the open phase: features, logits, top lists, tree tokens."""
-    import numpy as np
     _, n_rows, chain = dr.state()
     assert chain == n_chain and n_rows == len(orc.phase["f"])
     f_dev, l_dev = dr.rows("features", 0, n_rows), dr.rows("logits", 0, n_rows)
     f_ref, l_ref = np.array(orc.phase["f"]), np.array(orc.phase["logits"])
-    ef, el = _rel(f_dev, f_ref), _rel(l_dev, l_ref)
-    say(f"    rows {n_rows}: features rel err {ef:.2e}, logits rel err {el:.2e} (tol {tol:g})")
-    assert ef <= tol and el <= tol
+    pass_of = np.zeros(n_rows, dtype=int)
+    if parent is not None:
+        for bi, (a, _) in enumerate(orc.blocks):
+            if bi > 0:
+                pass_of[orc.rows_of[bi]] = depth[a] // orc.k
+    for p in range(int(pass_of.max()) + 1):
+        rows = np.nonzero(pass_of == p)[0]
+        ef, el = _rel(f_dev[rows], f_ref[rows]), _rel(l_dev[rows], l_ref[rows])
+        say(f"    pass {p}: {len(rows)} rows, features rel err {ef:.2e}, logits rel err {el:.2e} (tol {_tol_of_pass(tol, p):.2g})")
+        assert ef <= _tol_of_pass(tol, p) and el <= _tol_of_pass(tol, p)
     tops = dr.top(0, n_rows)
     for r in range(n_rows):
         np.testing.assert_array_equal(tops[r], do.top_m(l_dev[r], tops.shape[1]), err_msg=f"top list of row {r}")
@@ -103,6 +118,58 @@ def test_drafting_phases_elementwise(shape_name, k, tol):
         say(f"    tree of {len(parent)} nodes: {agree} tokens equal the oracle's own picks")
         assert tokens_dev[0] == toks[-1]
         assert agree >= len(parent) - 2
+    dr.close()
+    tgt.close()
+
+
+def test_wide_pass_and_degenerate_trees():
+    """A pass of more than 64 rows (the shared-activation GEMM kernel and its separate reduction launch),
+    a tree no deeper than k (no pass at all: the commit's rows give every token) and the one-node tree."""
+    import torch
+    s, lw, dw, tgt, dr = _make("tiny", 2, max_seq=400)
+    orc = do.DrafterOracle(s, lw, dw, 2, 400)
+    rng = np.random.default_rng(6)
+    shapes = [gen_tree(41, 205, [4, 10, 2, 1], 0), gen_tree(42, 9, [4, 1], 2), (np.array([-1]), np.array([0]), None)]
+    for phase, (n_new, tree) in enumerate(zip([4, 2, 1], shapes)):
+        feats = gen_features(200 + phase, n_new, s.hidden)
+        toks = rng.integers(0, s.vocab, n_new)
+        dr.commit(toks, torch.from_numpy(feats).cuda())
+        orc.commit(feats, toks)
+        parent, depth, _ = tree
+        rank = sibling_ranks(parent)
+        got = dr.draft_tree(parent, depth, rank, int(toks[-1]))
+        want = orc.draft(parent, depth, rank, int(toks[-1]), force_tokens=got)
+        say(f"  tree of {len(parent)} nodes: phase rows {dr.state()[1]}")
+        _check_phase(s, dr, orc, n_new, got, parent, depth, rank, 1e-4)
+        np.testing.assert_array_equal(got, want)
+        if phase == 0:
+            assert dr.state()[1] - n_new > 64
+    dr.close()
+    tgt.close()
+
+
+def test_benchmark_width_drafter_rows():
+    """The 7B width (hidden 4096, 32 heads, FFN 11008, vocabulary 32000) with k = 2 and a 64-node tree of
+    depth 8: what the benchmark times.  The oracle runs in fp32 on weights widened once."""
+    import torch
+    s, lw, dw, tgt, dr = _make("7b", 2, max_seq=256, layers=1)
+    orc = do.DrafterOracle(s, _oracle_weights(lw), _oracle_weights(dw), 2, 256, dtype=np.float32)
+    rng = np.random.default_rng(9)
+    trees = [gen_tree(51, 64, [8, 4, 2, 2, 1, 1, 1, 1], 8), gen_tree(52, 64, [6, 3, 2, 2, 2, 1, 1, 1], 8)]
+    for phase, (n_new, tree) in enumerate(zip([5, 2], trees)):
+        feats = gen_features(300 + phase, n_new, s.hidden)
+        toks = rng.integers(0, s.vocab, n_new)
+        dr.commit(toks, torch.from_numpy(feats).cuda())
+        say(f"  7b phase {phase}: commit {n_new} pairs {dr.last_ms():.3f} ms")
+        orc.commit(feats, toks)
+        parent, depth, _ = tree
+        rank = sibling_ranks(parent)
+        got = dr.draft_tree(parent, depth, rank, int(toks[-1]))
+        say(f"    tree: {dr.state()[1] - n_new} rows in {int(max(depth) + 1) // 2 - 1} passes, {dr.last_ms():.3f} ms")
+        want = orc.draft(parent, depth, rank, int(toks[-1]), force_tokens=got)
+        _check_phase(s, dr, orc, n_new, got, parent, depth, rank, 2e-2)
+        say(f"    {int(np.sum(got == want))} of {len(parent)} tokens equal the oracle's own picks")
+        assert int(np.sum(got == want)) >= len(parent) - 3
     dr.close()
     tgt.close()
 
