@@ -172,6 +172,56 @@ def decode_loop(fi, gpu, shape, L, root, n_nodes, branching, n_tokens, p_accept,
     }
 
 
+def draft_phase(fi, m, gpu, shape, L, k, n_new, n_nodes, branching, reps, seed):
+    """The drafting side of a decoding round at the same shape: take in n_new committed pairs (accepted tokens +
+    bonus token with the target's features), then fill a static n_nodes tree with the semi-autoregressive head
+    (k tokens per pass).  Random-init drafter, synthetic features: timing and traffic only."""
+    import torch
+    dw = fi.gen_drafter_weights(shape, seed=seed + 1)
+    dr = m.FalconDrafter(gpu, k)
+    dr.init_weights(dw)
+    rng = np.random.Generator(np.random.Philox(key=[seed, 7030]))
+    feats = torch.from_numpy(fi.gen_features(seed, L, shape.hidden)).cuda()
+    dr.commit(rng.integers(0, shape.vocab, L), feats)          # the drafter's own cache over the prompt
+    parent, depth, _ = fi.gen_tree(seed, n_nodes, branching, 0)
+    rank = fi.sibling_ranks(parent)
+    h, esz = shape.hidden, shape.elem_bytes()
+    layer = (shape.weight_params() - shape.vocab * h) // shape.n_layers
+    ih0, hh, head = 8 * h * h, 4 * h * h, shape.vocab * h
+    n_pass = (int(depth.max()) + k - 1) // k - 1                # tree passes (the commit's rows give the first k levels)
+    # per pass: lstm0.w_ih and lstm1.w_ih once, the two recurrent matrices once per level, the block, the head
+    commit_bytes = (ih0 + hh + 2 * hh * n_new + layer + head) * esz
+    levels = []
+    reach = depth.copy()
+    for i in range(len(parent) - 1, 0, -1):
+        reach[parent[i]] = max(reach[parent[i]], reach[i])
+    for p in range(1, n_pass + 1):
+        levels.append(max(min(k, int(reach[a] - depth[a])) for a in range(len(parent)) if depth[a] == p * k and reach[a] > depth[a]))
+    tree_bytes = sum((ih0 + hh + 2 * hh * lv + layer + head) * esz for lv in levels)
+    t_commit, t_tree = [], []
+    for r in range(reps + 2):
+        toks = rng.integers(0, shape.vocab, n_new)
+        dr.commit(toks, feats[:n_new])
+        tc = dr.last_ms()
+        dr.draft_tree(parent, depth, rank, int(toks[-1]))
+        if r >= 2:
+            t_commit.append(tc)
+            t_tree.append(dr.last_ms())
+    rows = dr.state()[1] - n_new
+    dr.close()
+    tc, tt = float(np.median(t_commit)), float(np.median(t_tree))
+    return {
+        "k": k, "committed_pairs_per_round": n_new, "tree_nodes": n_nodes, "tree_passes": n_pass, "tree_rows": int(rows),
+        "commit_ms": tc, "tree_ms": tt, "phase_ms": tc + tt,
+        "algorithmic_bytes": {"commit": commit_bytes, "tree": tree_bytes},
+        "achieved_GBps": {"commit": commit_bytes / (tc * 1e-3) / 1e9, "tree": tree_bytes / (tt * 1e-3) / 1e9},
+        "hbm_fraction": (commit_bytes + tree_bytes) / ((tc + tt) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "note": "device time between HIP events on the library's stream; bytes = every weight matrix once per launch that "
+                "multiplies by it (the recurrent LSTM matrices once per level: the rows of a level depend on the level before); "
+                "random-init drafter of the target's width (two LSTM layers 2h->h and h->h, one decoder block, shared LM head)",
+    }
+
+
 def kernel_source_hash():
     """sha256 over the library's HIP sources (what the counter runs under profiles/ were measured on)."""
     import hashlib
@@ -228,6 +278,10 @@ def main():
                     help="tokens of the multi-step decoding comparison (tree verification with a synthetic drafter "
                          "vs one token per step); 0 = skip")
     ap.add_argument("--loop-p", type=float, default=0.8, help="per-token acceptance probability of the synthetic drafter")
+    ap.add_argument("--draft-k", type=int, default=2, help="also time the drafting phase with this k (0: skip)")
+    ap.add_argument("--draft-new", type=int, default=4, help="committed pairs per round in the drafting-phase timing")
+    ap.add_argument("--draft-branching", default="8,4,2,2,1,1,1,1", help="static tree of the drafting-phase timing (depth 8, as in the paper's appendix)")
+    ap.add_argument("--draft-reps", type=int, default=10)
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run three device-to-device copies of this many MiB (a kernel of known HBM traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -252,6 +306,7 @@ def main():
     branching = (fi.random_branching(args.seed, args.nodes) if args.branching == "random"
                  else [int(x) for x in args.branching.split(",")])
     L, T = args.prefix, args.nodes
+    branching_draft = [int(x) for x in args.draft_branching.split(",")]
 
     t0 = time.time()
     weights = fi.gen_weights(shape, seed=args.seed)
@@ -363,6 +418,8 @@ def main():
                                   "note": "algorithmic K/V bytes over the per-launch HIP-event time of k_attn (profiling pass)"}
     if args.loop_tokens > 0:
         out["decode_loop"] = decode_loop(fi, gpu, shape, L, root, T, branching, args.loop_tokens, args.loop_p, args.seed)
+    if args.draft_k > 0:
+        out["draft_phase"] = draft_phase(fi, m, gpu, shape, L, args.draft_k, args.draft_new, T, branching_draft, args.draft_reps, args.seed)
     traffic, traffic_src = measured_traffic(kname, args, shape)
     out["roofline"]["traffic"] = traffic
     out["roofline"]["traffic_note"] = (

@@ -260,7 +260,7 @@ int fv_last_step_ms(fv_ctx* ctx, float* ms);
  *   fv_draft_commit (the pairs the target fixed since the last phase: n = accepted + 1 after a
  *   verification step, the whole prompt after prefill), then at most one fv_draft_tree.
  * Limits: k <= FV_DRAFT_MAX_K; rank < FV_DRAFT_MAX_M; at most 256 rows per phase (rows of the
- *   commit's last piece + rows of all blocks); vocab <= 65536.
+ *   commit's last piece + rows of all blocks); vocab <= 32768.
  * The drafter shares the target context's stream, embedding table and LM head: the target context
  * must outlive it and its weights must be set.  Calls are synchronous on return. */
 #define FV_DRAFT_MAX_K 8

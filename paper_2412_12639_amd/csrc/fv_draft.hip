@@ -92,7 +92,7 @@ int fv_drafter_workspace_bytes(const fv_cfg* target_cfg, size_t* out_bytes) {
     if (!out_bytes) return FV_E_BAD_ARG;
     int rc = check_cfg(target_cfg);
     if (rc) return rc;
-    if (target_cfg->vocab > 65536) return FV_E_BAD_ARG;   // the top-list kernel keeps a row of logits in registers
+    if (target_cfg->vocab > 32768) return FV_E_BAD_ARG;   // the top-list kernel keeps a row of logits in registers
     DraftLayout L;
     make_draft_layout(*target_cfg, n_workgroups(), L);
     *out_bytes = L.total;
@@ -103,7 +103,7 @@ int fv_drafter_create(fv_ctx* target, int32_t k, void* dev_arena, size_t arena_b
     if (!out) return FV_E_BAD_ARG;
     *out = nullptr;
     if (!target || k < 1 || k > FV_DRAFT_KMAX || !dev_arena || ((uintptr_t)dev_arena & 255)) return FV_E_BAD_ARG;
-    if (target->cfg.vocab > 65536) return FV_E_BAD_ARG;
+    if (target->cfg.vocab > 32768) return FV_E_BAD_ARG;
     fv_drafter* d = new (std::nothrow) fv_drafter();
     if (!d) return FV_E_BAD_ARG;
     d->target = target;

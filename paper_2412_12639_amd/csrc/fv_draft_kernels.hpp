@@ -218,11 +218,12 @@ static __global__ __launch_bounds__(256) void k_draft_out(DraftOutArgs a) {
         a.fout[(size_t)(a.r0 + t) * a.h + f] = a.x[((size_t)(f >> 2) * a.Tp + t) * 4 + (f & 3)];
 }
 
-// Top-m of one row of logits: descending value, lower token id first among equals.  A thread keeps
-// its 4 * NV4 values in registers; the candidates come out one per round: every thread offers its
-// best value that comes after the last winner in that order, a workgroup-wide reduction picks the
-// winner, and only the wavefront that held it looks for its next offer.  A row that holds a NaN or
-// an infinity has no order: its list is filled with -1.
+// Top-m of one row of logits: descending value, lower token id first among equals (a total order, so
+// the result is unique).  A thread keeps its 16 * NV4 values in registers.  The 32nd best of the 256
+// per-thread bests is a threshold that at least 32 values reach, and every value that reaches it sits in
+// one of the 32 threads whose best does: at most 32 * 16 * NV4 candidates, usually a few dozen.  They are
+// collected in LDS (in any order) and each finds its place by counting the candidates ahead of it.
+// A row that holds a NaN or an infinity has no order: its list is filled with -1 and *bad is set.
 struct TopmArgs {
     const float* logits;   // [n][Vpad] (row t of this pass)
     int32_t* top_tok;      // [256 + KMAX][FV_DRAFT_MMAX] by output row id
@@ -231,78 +232,75 @@ struct TopmArgs {
     int r0, n, V, Vpad, m;
 };
 
-__device__ __forceinline__ bool topm_after(float v, int i, float lv, int li) { return v < lv || (v == lv && i > li); }
 __device__ __forceinline__ bool topm_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
 template <int NV4>
 static __global__ __launch_bounds__(256) void k_topm(TopmArgs a) {
-    __shared__ float sv[4];
-    __shared__ int si[4];
-    __shared__ int sbad[4];
-    __shared__ float win_v;
-    __shared__ int win_i;
-    const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6;
+    constexpr int CAP = 32 * 4 * NV4;
+    __shared__ float best_v[256];
+    __shared__ int best_i[256];
+    __shared__ float cand_v[CAP];
+    __shared__ int cand_i[CAP];
+    __shared__ int n_cand, any_bad, thr_i;
+    __shared__ float thr_v;
+    const int t = blockIdx.x, tid = threadIdx.x;
     if (t >= a.n) return;
     const float* row = a.logits + (size_t)t * a.Vpad;
+    if (tid == 0) { n_cand = 0; any_bad = 0; }
     float4 x[NV4];
     bool bad = false;
+    float bv = -INFINITY;
+    int bi = 0x40000000 + tid;   // a thread with no value at all still has a distinct place in the order, behind every token
 #pragma unroll
     for (int k = 0; k < NV4; ++k) {
         const int v = (tid + 256 * k) * 4;
-        x[k] = (v < a.V) ? *(const float4*)(row + v) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);   // Vpad is a multiple of 32
+        x[k] = (v < a.V) ? *(const float4*)(row + v) : make_float4(0.f, 0.f, 0.f, 0.f);   // Vpad is a multiple of 32
         const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-            if (v + c < a.V) bad = bad || !(__builtin_fabsf(xs[c]) < INFINITY);   // entries at or above V are never offered
+            if (v + c < a.V) {
+                bad = bad || !(__builtin_fabsf(xs[c]) < INFINITY);
+                if (topm_better(xs[c], v + c, bv, bi)) { bv = xs[c]; bi = v + c; }
+            }
     }
-    const bool wbad = __any(bad);
-    if ((tid & 63) == 0) sbad[wave] = wbad ? 1 : 0;
+    best_v[tid] = bv;
+    best_i[tid] = bi;
+    __syncthreads();
+    if (bad) any_bad = 1;
+    int ahead = 0;
+    for (int j = 0; j < 256; ++j) ahead += topm_better(best_v[j], best_i[j], bv, bi) ? 1 : 0;
+    if (ahead == FV_DRAFT_MMAX - 1) { thr_v = bv; thr_i = bi; }   // exactly one thread: the order is total
     __syncthreads();
     int32_t* out_t = a.top_tok + (size_t)(a.r0 + t) * FV_DRAFT_MMAX;
     float* out_v = a.top_val + (size_t)(a.r0 + t) * FV_DRAFT_MMAX;
-    if (sbad[0] | sbad[1] | sbad[2] | sbad[3]) {
-        if (tid < FV_DRAFT_MMAX) { out_t[tid] = -1; out_v[tid] = 0.f; }
+    if (tid < FV_DRAFT_MMAX) { out_t[tid] = -1; out_v[tid] = 0.f; }   // fewer than m tokens, or a non-finite row
+    if (any_bad) {
         if (tid == 0) *a.bad = 1;
         return;
     }
-    float lv = INFINITY;   // the last winner; everything comes after (+inf, -1)
-    int li = -1;
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    bool rescan = true;
-    for (int round = 0; round < a.m; ++round) {
-        if (rescan) {   // wavefront-uniform
-            bv = -INFINITY; bi = 0x7fffffff;
+    const float tv = thr_v;
+    const int ti = thr_i;
+    if (ahead < FV_DRAFT_MMAX) {   // only these threads can hold values that reach the threshold
 #pragma unroll
-            for (int k = 0; k < NV4; ++k) {
-                const int v = (tid + 256 * k) * 4;
-                const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+        for (int k = 0; k < NV4; ++k) {
+            const int v = (tid + 256 * k) * 4;
+            const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (v + c < a.V && topm_after(xs[c], v + c, lv, li) && topm_better(xs[c], v + c, bv, bi)) { bv = xs[c]; bi = v + c; }
-            }
+            for (int c = 0; c < 4; ++c)
+                if (v + c < a.V && !topm_better(tv, ti, xs[c], v + c)) {   // not behind the threshold
+                    const int pos = atomicAdd(&n_cand, 1);
+                    if (pos < CAP) { cand_v[pos] = xs[c]; cand_i[pos] = v + c; }
+                }
         }
-        float wv = bv;
-        int wi = bi;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(wv, off);
-            const int oi = __shfl_xor(wi, off);
-            if (topm_better(ov, oi, wv, wi)) { wv = ov; wi = oi; }
-        }
-        if ((tid & 63) == 0) { sv[wave] = wv; si[wave] = wi; }
-        __syncthreads();
-        if (tid == 0) {
-            float fv = sv[0]; int fi = si[0];
-            for (int w = 1; w < 4; ++w) if (topm_better(sv[w], si[w], fv, fi)) { fv = sv[w]; fi = si[w]; }
-            win_v = fv; win_i = fi;
-            out_t[round] = (fi == 0x7fffffff) ? -1 : fi;   // fewer than m tokens in the vocabulary
-            out_v[round] = fv;
-        }
-        __syncthreads();
-        lv = win_v; li = win_i;
-        rescan = (si[wave] == li);   // the wavefront that held the winner needs a new offer
-        __syncthreads();
+    }
+    __syncthreads();
+    const int C = n_cand < CAP ? n_cand : CAP;   // n_cand cannot exceed CAP: 32 threads of 16 * NV4 values each
+    for (int c = tid; c < C; c += 256) {
+        const float v = cand_v[c];
+        const int i = cand_i[c];
+        int r = 0;
+        for (int j = 0; j < C; ++j) r += topm_better(cand_v[j], cand_i[j], v, i) ? 1 : 0;
+        if (r < a.m && r < FV_DRAFT_MMAX) { out_t[r] = i; out_v[r] = v; }
     }
 }
 

@@ -169,8 +169,7 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
         ta.top_val = d->at<float>(dl.off_top_val); ta.bad = d->at<int32_t>(dl.off_bad);
         ta.r0 = ps.r0; ta.n = n; ta.V = cf.vocab; ta.Vpad = ly.Vpad; ta.m = FV_DRAFT_MMAX;
         if (cf.vocab <= 8192) hipLaunchKernelGGL((k_topm<8>), dim3(n), dim3(256), 0, st, ta);
-        else if (cf.vocab <= 32768) hipLaunchKernelGGL((k_topm<32>), dim3(n), dim3(256), 0, st, ta);
-        else hipLaunchKernelGGL((k_topm<64>), dim3(n), dim3(256), 0, st, ta);
+        else hipLaunchKernelGGL((k_topm<32>), dim3(n), dim3(256), 0, st, ta);   // vocab <= 32768, checked at creation
     }
     if (ps.n_exp > 0) {
         ExpandArgs ea;

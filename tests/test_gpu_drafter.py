@@ -174,6 +174,46 @@ def test_benchmark_width_drafter_rows():
     tgt.close()
 
 
+@pytest.mark.parametrize("head", ["ties", "zero"])
+def test_top_lists_with_equal_logits(head):
+    """Equal logits are ordered by token id: three LM-head rows made identical (and large, so that they
+    often make the list), and an all-zero head (every logit equal: the list is 0, 1, 2, ...)."""
+    import torch
+    from paper_2412_12639_amd.binding import FalconDrafter, FalconVerifier
+    s = shape_by_name("tiny")
+    lw = gen_weights(s, seed=2)
+    lw["lm_head"] = lw["lm_head"].copy()
+    if head == "ties":
+        lw["lm_head"][[100, 300]] = lw["lm_head"][7]
+        lw["lm_head"][[7, 100, 300]] *= 6.0
+    else:
+        lw["lm_head"][:] = 0.0
+    dw = gen_drafter_weights(s, seed=3)
+    tgt = FalconVerifier(s, 64, 64)
+    tgt.init_weights(lw)
+    dr = FalconDrafter(tgt, 2)
+    dr.init_weights(dw)
+    feats = gen_features(4, 9, s.hidden)
+    toks = np.random.default_rng(4).integers(0, s.vocab, 9)
+    dr.commit(toks, torch.from_numpy(feats).cuda())
+    logits, tops = dr.rows("logits", 0, 9), dr.top(0, 9)
+    for r in range(9):
+        np.testing.assert_array_equal(tops[r], do.top_m(logits[r], 32))
+        if head == "zero":
+            assert list(tops[r]) == list(range(32))
+        else:
+            assert logits[r][7] == logits[r][100] == logits[r][300]
+            lst = tops[r].tolist()
+            if 7 in lst and lst.index(7) + 2 < len(lst):     # the three equal logits are neighbours, in id order
+                assert lst[lst.index(7):lst.index(7) + 3] == [7, 100, 300]
+    parent, depth, _ = gen_tree(3, 20, [6, 3, 1], 0)
+    got = dr.draft_tree(parent, depth, sibling_ranks(parent), int(toks[-1]))
+    if head == "zero":
+        np.testing.assert_array_equal(got[1:], sibling_ranks(parent)[1:])   # rank r takes token r everywhere
+    dr.close()
+    tgt.close()
+
+
 def test_long_commit_in_pieces_and_errors():
     import torch
     from paper_2412_12639_amd.binding import FvError
