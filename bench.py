@@ -172,7 +172,7 @@ def decode_loop(fi, gpu, shape, L, root, n_nodes, branching, n_tokens, p_accept,
     }
 
 
-def draft_phase(fi, m, gpu, shape, L, k, n_new, n_nodes, branching, reps, seed):
+def draft_phase(fi, m, gpu, shape, L, k, n_new, n_nodes, branching, reps, seed, gpu_weights=None, cpu_too=False):
     """The drafting side of a decoding round at the same shape: take in n_new committed pairs (accepted tokens +
     bonus token with the target's features), then fill a static n_nodes tree with the semi-autoregressive head
     (k tokens per pass).  Random-init drafter, synthetic features: timing and traffic only."""
@@ -210,7 +210,24 @@ def draft_phase(fi, m, gpu, shape, L, k, n_new, n_nodes, branching, reps, seed):
     rows = dr.state()[1] - n_new
     dr.close()
     tc, tt = float(np.median(t_commit)), float(np.median(t_tree))
+    cpu = None
+    if cpu_too:
+        # the drafting oracle on the same phase (fp32 on weights widened once; it is not tuned for this)
+        from oracle import drafter_oracle as do
+        widen = lambda w: {n: ((a.astype(np.uint32) << 16).view(np.float32) if a.dtype == np.uint16 else a) for n, a in w.items()}
+        lw = widen({"embed": gpu_weights["embed"], "lm_head": gpu_weights["lm_head"]})
+        orc = do.DrafterOracle(shape, lw, widen(dw), k, 64, dtype=np.float32)
+        f = fi.gen_features(seed, n_new + k, shape.hidden)
+        orc.commit(f[:k], rng.integers(0, shape.vocab, k))
+        t0 = time.perf_counter()
+        toks = rng.integers(0, shape.vocab, n_new)
+        orc.commit(f[k:], toks)
+        orc.draft(parent, depth, rank, int(toks[-1]))
+        cores, model = host_cpu()
+        cpu = {"phase_s": time.perf_counter() - t0, "kind": "oracle", "host": {"logical_cores_available": cores, "cpu_model": model},
+               "sample": "numpy fp32 drafting oracle, one phase (the same commit and tree) on an empty prefix"}
     return {
+        "cpu_baseline": cpu,
         "k": k, "committed_pairs_per_round": n_new, "tree_nodes": n_nodes, "tree_passes": n_pass, "tree_rows": int(rows),
         "commit_ms": tc, "tree_ms": tt, "phase_ms": tc + tt,
         "algorithmic_bytes": {"commit": commit_bytes, "tree": tree_bytes},
@@ -419,7 +436,9 @@ def main():
     if args.loop_tokens > 0:
         out["decode_loop"] = decode_loop(fi, gpu, shape, L, root, T, branching, args.loop_tokens, args.loop_p, args.seed)
     if args.draft_k > 0:
-        out["draft_phase"] = draft_phase(fi, m, gpu, shape, L, args.draft_k, args.draft_new, T, branching_draft, args.draft_reps, args.seed)
+        out["draft_phase"] = draft_phase(fi, m, gpu, shape, L, args.draft_k, args.draft_new, T, branching_draft, args.draft_reps, args.seed,
+                                         gpu_weights=weights, cpu_too=args.cpu_layers != 0)
+        out["draft_phase"]["round_ms_with_verification"] = out["draft_phase"]["phase_ms"] + float(np.median(dev_ms))
     traffic, traffic_src = measured_traffic(kname, args, shape)
     out["roofline"]["traffic"] = traffic
     out["roofline"]["traffic_note"] = (
