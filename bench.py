@@ -439,6 +439,14 @@ def main():
         out["draft_phase"] = draft_phase(fi, m, gpu, shape, L, args.draft_k, args.draft_new, T, branching_draft, args.draft_reps, args.seed,
                                          gpu_weights=weights, cpu_too=args.cpu_layers != 0)
         out["draft_phase"]["round_ms_with_verification"] = out["draft_phase"]["phase_ms"] + float(np.median(dev_ms))
+        if "decode_loop" in out:
+            # the loop's per-token time with this drafter's measured cost added to every round (a random-init drafter
+            # cannot be accepted, so the acceptance length stays the synthetic one: context, like the loop itself)
+            dl = out["decode_loop"]
+            per_round = dl["tokens"] / max(1, dl["steps"])
+            with_draft = dl["tree_verify_ms_per_token"] + out["draft_phase"]["phase_ms"] / per_round
+            dl["tree_verify_plus_drafting_ms_per_token"] = with_draft
+            dl["speedup_with_drafting_cost"] = dl["single_token_ms_per_token"] / with_draft
     traffic, traffic_src = measured_traffic(kname, args, shape)
     out["roofline"]["traffic"] = traffic
     out["roofline"]["traffic_note"] = (

@@ -219,10 +219,11 @@ static __global__ __launch_bounds__(256) void k_draft_out(DraftOutArgs a) {
 }
 
 // Top-m of one row of logits: descending value, lower token id first among equals (a total order, so
-// the result is unique).  A thread keeps its 16 * NV4 values in registers.  The 32nd best of the 256
-// per-thread bests is a threshold that at least 32 values reach, and every value that reaches it sits in
-// one of the 32 threads whose best does: at most 32 * 16 * NV4 candidates, usually a few dozen.  They are
-// collected in LDS (in any order) and each finds its place by counting the candidates ahead of it.
+// the result is unique).  One workgroup of 1024 threads per row; a thread keeps 32 values in registers
+// (vocabulary <= 32768).  The second best of every wavefront's 64 per-thread bests gives 32 values that
+// reach the smallest of these sixteen, so that one is a threshold that at least 32 values reach: the
+// values that reach it (usually about a hundred) are collected in LDS and ranked by counting.  If there
+// are more than 256 of them (many equal logits), the list is instead drawn one winner per round.
 // A row that holds a NaN or an infinity has no order: its list is filled with -1 and *bad is set.
 struct TopmArgs {
     const float* logits;   // [n][Vpad] (row t of this pass)
@@ -232,44 +233,63 @@ struct TopmArgs {
     int r0, n, V, Vpad, m;
 };
 
-__device__ __forceinline__ bool topm_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+#define FV_TOPM_THREADS 1024
+#define FV_TOPM_FAST 256   // candidates the counting path holds
 
-template <int NV4>
-static __global__ __launch_bounds__(256) void k_topm(TopmArgs a) {
-    constexpr int CAP = 32 * 4 * NV4;
-    __shared__ float best_v[256];
-    __shared__ int best_i[256];
-    __shared__ float cand_v[CAP];
-    __shared__ int cand_i[CAP];
-    __shared__ int n_cand, any_bad, thr_i;
-    __shared__ float thr_v;
-    const int t = blockIdx.x, tid = threadIdx.x;
+// (value, token id) as one 64-bit integer, larger = earlier in the list; v is finite and not -0.  0 = no value.
+__device__ __forceinline__ unsigned long long topm_key(float v, int i) {
+    uint32_t u = __float_as_uint(v);
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;
+    return ((unsigned long long)u << 32) | (uint32_t)(0x7FFFFFFF - i);
+}
+__device__ __forceinline__ float topm_key_value(unsigned long long key) {
+    uint32_t u = (uint32_t)(key >> 32);
+    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
+    return __uint_as_float(u);
+}
+__device__ __forceinline__ int topm_key_token(unsigned long long key) { return 0x7FFFFFFF - (int)(uint32_t)key; }
+__device__ __forceinline__ unsigned long long topm_wave_max(unsigned long long k) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const unsigned long long o = ((unsigned long long)(uint32_t)__shfl_xor((int)(k >> 32), off) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)k, off);
+        k = o > k ? o : k;
+    }
+    return k;
+}
+
+static __global__ __launch_bounds__(FV_TOPM_THREADS) void k_topm(TopmArgs a) {
+    __shared__ unsigned long long wave_key[16];
+    __shared__ unsigned long long cand[FV_TOPM_FAST];
+    __shared__ int rank_of[FV_TOPM_FAST];
+    __shared__ int n_cand, any_bad;
+    const int t = blockIdx.x, tid = threadIdx.x, wave = tid >> 6;
     if (t >= a.n) return;
     const float* row = a.logits + (size_t)t * a.Vpad;
     if (tid == 0) { n_cand = 0; any_bad = 0; }
-    float4 x[NV4];
+    if (tid < FV_TOPM_FAST) rank_of[tid] = 0;
+    float x[32];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int v = (tid + FV_TOPM_THREADS * k) * 4;
+        const float4 q = (v < a.V) ? *(const float4*)(row + v) : make_float4(0.f, 0.f, 0.f, 0.f);   // Vpad is a multiple of 32
+        x[4 * k] = q.x + 0.f; x[4 * k + 1] = q.y + 0.f; x[4 * k + 2] = q.z + 0.f; x[4 * k + 3] = q.w + 0.f;   // -0 -> +0: equal values, one key
+    }
+    auto token_of = [&](int e) { return (tid + FV_TOPM_THREADS * (e >> 2)) * 4 + (e & 3); };   // ascending in e
     bool bad = false;
     float bv = -INFINITY;
-    int bi = 0x40000000 + tid;   // a thread with no value at all still has a distinct place in the order, behind every token
+    int bi = -1;
 #pragma unroll
-    for (int k = 0; k < NV4; ++k) {
-        const int v = (tid + 256 * k) * 4;
-        x[k] = (v < a.V) ? *(const float4*)(row + v) : make_float4(0.f, 0.f, 0.f, 0.f);   // Vpad is a multiple of 32
-        const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (v + c < a.V) {
-                bad = bad || !(__builtin_fabsf(xs[c]) < INFINITY);
-                if (topm_better(xs[c], v + c, bv, bi)) { bv = xs[c]; bi = v + c; }
-            }
-    }
-    best_v[tid] = bv;
-    best_i[tid] = bi;
-    __syncthreads();
-    if (bad) any_bad = 1;
-    int ahead = 0;
-    for (int j = 0; j < 256; ++j) ahead += topm_better(best_v[j], best_i[j], bv, bi) ? 1 : 0;
-    if (ahead == FV_DRAFT_MMAX - 1) { thr_v = bv; thr_i = bi; }   // exactly one thread: the order is total
+    for (int e = 0; e < 32; ++e)
+        if (token_of(e) < a.V) {
+            bad = bad || !(__builtin_fabsf(x[e]) < INFINITY);
+            if (x[e] > bv) { bv = x[e]; bi = token_of(e); }   // the first of equal values stays
+        }
+    // the wavefront's best and second best of its 64 thread bests
+    const unsigned long long my_key = (bi >= 0 && !bad) ? topm_key(bv, bi) : 0ull;
+    const unsigned long long w1 = topm_wave_max(my_key);
+    const unsigned long long w2 = topm_wave_max(my_key == w1 ? 0ull : my_key);   // keys of real values are distinct
+    if ((tid & 63) == 0) wave_key[wave] = w2;
+    if (__any(bad) && (tid & 63) == 0) any_bad = 1;   // written before the barrier, read after it (only ever set to 1)
     __syncthreads();
     int32_t* out_t = a.top_tok + (size_t)(a.r0 + t) * FV_DRAFT_MMAX;
     float* out_v = a.top_val + (size_t)(a.r0 + t) * FV_DRAFT_MMAX;
@@ -278,29 +298,60 @@ static __global__ __launch_bounds__(256) void k_topm(TopmArgs a) {
         if (tid == 0) *a.bad = 1;
         return;
     }
-    const float tv = thr_v;
-    const int ti = thr_i;
-    if (ahead < FV_DRAFT_MMAX) {   // only these threads can hold values that reach the threshold
+    unsigned long long thr = wave_key[0];
 #pragma unroll
-        for (int k = 0; k < NV4; ++k) {
-            const int v = (tid + 256 * k) * 4;
-            const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w};
+    for (int w = 1; w < 16; ++w) thr = wave_key[w] < thr ? wave_key[w] : thr;   // 0 if some wavefront has fewer than two values: everything is a candidate
+    const float tv = topm_key_value(thr);
+    const int ti = topm_key_token(thr);
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (v + c < a.V && !topm_better(tv, ti, xs[c], v + c)) {   // not behind the threshold
-                    const int pos = atomicAdd(&n_cand, 1);
-                    if (pos < CAP) { cand_v[pos] = xs[c]; cand_i[pos] = v + c; }
-                }
+    for (int e = 0; e < 32; ++e) {
+        const int i = token_of(e);
+        const bool hit = i < a.V && (thr == 0ull || x[e] > tv || (x[e] == tv && i <= ti));
+        if (hit) {
+            const int pos = atomicAdd(&n_cand, 1);
+            if (pos < FV_TOPM_FAST) cand[pos] = topm_key(x[e], i);
         }
     }
     __syncthreads();
-    const int C = n_cand < CAP ? n_cand : CAP;   // n_cand cannot exceed CAP: 32 threads of 16 * NV4 values each
-    for (int c = tid; c < C; c += 256) {
-        const float v = cand_v[c];
-        const int i = cand_i[c];
-        int r = 0;
-        for (int j = 0; j < C; ++j) r += topm_better(cand_v[j], cand_i[j], v, i) ? 1 : 0;
-        if (r < a.m && r < FV_DRAFT_MMAX) { out_t[r] = i; out_v[r] = v; }
+    const int C = n_cand;
+    if (C <= FV_TOPM_FAST) {
+        // rank by counting: candidate c = tid % 256, a quarter of the comparisons per thread
+        const int c = tid & (FV_TOPM_FAST - 1), part = tid >> 8;
+        if (c < C) {
+            const unsigned long long key = cand[c];
+            int ahead = 0;
+            for (int j = part; j < C; j += 4) ahead += cand[j] > key ? 1 : 0;
+            if (ahead) atomicAdd(&rank_of[c], ahead);
+        }
+        __syncthreads();
+        if (tid < C) {
+            const int r = rank_of[tid];
+            if (r < a.m && r < FV_DRAFT_MMAX) { out_t[r] = topm_key_token(cand[tid]); out_v[r] = topm_key_value(cand[tid]); }
+        }
+        return;
+    }
+    // many values reach the threshold (equal logits): one winner per round, each thread offering its best value
+    // that comes after the last winner
+    unsigned long long last = ~0ull;
+    const int rounds = a.m < FV_DRAFT_MMAX ? a.m : FV_DRAFT_MMAX;
+    for (int round = 0; round < rounds; ++round) {
+        unsigned long long offer = 0ull;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const int i = token_of(e);
+            const unsigned long long k = i < a.V ? topm_key(x[e], i) : 0ull;
+            offer = (k < last && k > offer) ? k : offer;
+        }
+        const unsigned long long w = topm_wave_max(offer);
+        __syncthreads();   // the previous round's wave_key has been read by everyone
+        if ((tid & 63) == 0) wave_key[wave] = w;
+        __syncthreads();
+        unsigned long long win = wave_key[0];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) win = wave_key[q] > win ? wave_key[q] : win;
+        if (win == 0ull) break;   // fewer than m tokens
+        if (tid == 0) { out_t[round] = topm_key_token(win); out_v[round] = topm_key_value(win); }
+        last = win;
     }
 }
 

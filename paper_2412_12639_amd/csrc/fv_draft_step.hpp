@@ -168,8 +168,7 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
         ta.logits = d->at<float>(dl.off_logits) + (size_t)ps.r0 * ly.Vpad; ta.top_tok = d->at<int32_t>(dl.off_top_tok);
         ta.top_val = d->at<float>(dl.off_top_val); ta.bad = d->at<int32_t>(dl.off_bad);
         ta.r0 = ps.r0; ta.n = n; ta.V = cf.vocab; ta.Vpad = ly.Vpad; ta.m = FV_DRAFT_MMAX;
-        if (cf.vocab <= 8192) hipLaunchKernelGGL((k_topm<8>), dim3(n), dim3(256), 0, st, ta);
-        else hipLaunchKernelGGL((k_topm<32>), dim3(n), dim3(256), 0, st, ta);   // vocab <= 32768, checked at creation
+        hipLaunchKernelGGL(k_topm, dim3(n), dim3(FV_TOPM_THREADS), 0, st, ta);   // vocab <= 32768, checked at creation
     }
     if (ps.n_exp > 0) {
         ExpandArgs ea;
