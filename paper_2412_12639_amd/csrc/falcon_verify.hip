@@ -202,6 +202,7 @@ void make_layout(const fv_cfg& c, int n_wg, Layout& L, bool own_head, size_t min
     L.off_stepin = take(3 * FV_MAX_TREE * 4);
     L.off_mask = take(FV_MAX_TREE * 4 * 8);
     L.off_pos = take(FV_MAX_TREE * 4);
+    L.off_anc = take(FV_MAX_TREE * (FV_CANON_DEPTH + 1));
     L.off_rope = take((size_t)FV_MAX_TREE * (d / 2) * 8);
     L.off_am = take(FV_MAX_TREE * 4);
     L.off_res = take(sizeof(FvResult));
@@ -388,6 +389,7 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
         }
     }
     { const char* e = getenv("FV_GEMM_FIX"); c->gemm_fix = e ? atoi(e) : 1; }
+    { const char* e = getenv("FV_ATTN"); c->attn_canon = !(e && !strcmp(e, "legacy")); }
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipHostMalloc((void**)&c->h_res, sizeof(FvResult), hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
@@ -419,6 +421,7 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
         a.part = c->at<float>(ly.off_part); a.part_bytes = (unsigned)ly.part_bytes;
         a.tickets = c->at<int>(ly.off_tickets); a.ticket_bytes = (size_t)ngmax * 4;
         a.apart = c->at<float>(ly.off_apart); a.atick = c->at<int>(ly.off_atick); a.atick_bytes = (size_t)cfg->n_q_heads * 8 * 4;
+        a.aslots = 32;   // the area holds 8 node blocks x 8 parts per head: 32 triples for each of a 64-row step's two blocks
         c->scr = &c->scr_arena;
         // the same buffers for steps of up to 64 rows (direct and paired GEMM forms, two 32-node attention
         // blocks per head, up to 8 key parts each) inside the static array, if they fit
@@ -439,6 +442,7 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
             t.part = (float*)(base + o_part); t.part_bytes = (unsigned)pb;
             t.tickets = (int*)(base + o_tick); t.ticket_bytes = a.ticket_bytes;
             t.apart = (float*)(base + o_ap); t.atick = (int*)(base + o_at); t.atick_bytes = a.atick_bytes;
+            t.aslots = 8;
         }
     }
     *out = c;
@@ -535,6 +539,12 @@ int fv_verify_tree_noalloc(fv_ctx* c, const int32_t* tok, const int32_t* parent,
     // limits of the static scratch: steps of up to 64 rows, and a shape whose partial tiles fit
     if (n > FV_NOALLOC_MAX_NODES || !c->scr_static.part) return FV_E_SCRATCH_LIMIT;
     const StepScratch& t = c->scr_static;
+    if (c->attn_canon) {   // the attention's far parts must fit its slots too (the step must compute what fv_verify_tree computes)
+        int maxdepth = 0;
+        for (int i = 0; i < n; ++i) maxdepth = std::max(maxdepth, (int)depth[i]);
+        const int pb = (c->cur_len + maxdepth) >> 5;
+        if (maxdepth <= FV_CANON_DEPTH && canon_parts(pb > 0 ? pb - 1 : 0) + 1 > t.aslots) return FV_E_SCRATCH_LIMIT;
+    }
     // the array keeps the last call's contents (any context on this GPU): tickets must start at zero
     const size_t nt = t.ticket_bytes / 4, na = t.atick_bytes / 4;
     hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, c->stream, (uint32_t*)t.tickets, 0u, nt);

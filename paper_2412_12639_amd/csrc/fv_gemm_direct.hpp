@@ -108,16 +108,20 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     // the weight/activation prefetch right behind them, the cross-thread reduction after that.
     float4 s4 = make_float4(0.f, 0.f, 0.f, 0.f);
     float4 sv[8];   // the first (usually only) eight rows of this thread: summed after the prefetch is out
+    // The partial sums of a token are added in an order that does not depend on the number of tokens
+    // (SL slices whatever Tp is: with 32 tokens half of the threads sit this out), so a row's factor,
+    // and with it everything computed from it, is bitwise the same in a step of 1 and of 64 rows.
+    static_assert(TB <= 2, "the statistics reduction is laid out for up to 64 tokens");
     if (with_norm) {
-        constexpr int C4 = Tp / 4, SL = 256 / C4;
+        constexpr int C4 = Tp / 4, SL = 16;
         const int col = tid % C4, sl = tid / C4;
         const float4* sp = (const float4*)a.ssq_in + col;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int i = sl + k * SL;
-            sv[k] = (i < a.n_ssq) ? sp[(size_t)i * C4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            sv[k] = (sl < SL && i < a.n_ssq) ? sp[(size_t)i * C4] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        for (int i0 = sl + 8 * SL; i0 < a.n_ssq; i0 += 8 * SL) {   // more than 8 rows per thread (hidden size above 256 * SL)
+        for (int i0 = sl + 8 * SL; sl < SL && i0 < a.n_ssq; i0 += 8 * SL) {   // more than 8 rows per thread (hidden size above 256 * SL)
             float4 v[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
@@ -197,11 +201,11 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     FV_TS(4)
 
     if (with_norm) {
-        constexpr int C4 = Tp / 4, SL = 256 / C4;
+        constexpr int C4 = Tp / 4, SL = 16;
         const int col = tid % C4, sl = tid / C4;
 #pragma unroll
         for (int k = 0; k < 8; ++k) { s4.x += sv[k].x; s4.y += sv[k].y; s4.z += sv[k].z; s4.w += sv[k].w; }
-        ((float4*)red_lds)[sl * C4 + col] = s4;
+        if (sl < SL) ((float4*)red_lds)[sl * C4 + col] = s4;
         __syncthreads();
         if (tid < Tp) {
             float tot = 0.f;

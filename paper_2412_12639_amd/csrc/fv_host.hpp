@@ -52,7 +52,7 @@ struct Layout {
     size_t off_k = 0, off_v = 0, kv_layer_bytes = 0;
     size_t off_x = 0, off_xb = 0, off_q = 0, off_qlo = 0, off_attn = 0, off_act = 0, off_logits = 0;
     size_t off_ssq = 0, off_rinv = 0, off_part = 0, part_bytes = 0, off_tickets = 0;
-    size_t off_stepin = 0, off_mask = 0, off_pos = 0, off_rope = 0, off_am = 0, off_res = 0;
+    size_t off_stepin = 0, off_mask = 0, off_pos = 0, off_anc = 0, off_rope = 0, off_am = 0, off_res = 0;
     size_t off_kvread = 0, off_stage = 0, stage_bytes = 0;
     size_t off_apart = 0, off_atick = 0, off_zeros = 0, off_feat = 0;
     size_t off_unif = 0, off_pwork = 0;   // non-greedy acceptance: uniforms [2][256] fp64, working distribution [Vpad] fp64
@@ -75,6 +75,7 @@ enum StepMode { STEP_VERIFY = 0, STEP_PREFILL_MID = 1, STEP_PREFILL_LAST = 2, ST
 struct StepScratch {
     float* part = nullptr; unsigned part_bytes = 0; int* tickets = nullptr; size_t ticket_bytes = 0;
     float* apart = nullptr; int* atick = nullptr; size_t atick_bytes = 0;
+    int aslots = 0;   // key-part triples per (head, 32-row block) item that apart holds for a step of up to 64 rows
 };
 
 struct fv_ctx {
@@ -98,6 +99,7 @@ struct fv_ctx {
     float last_ms = 0.f;
     bool profiling = false;
     int kind[GM_COUNT];       // GemmKind per matrix, used up to 64 tokens
+    bool attn_canon = true;      // step-independent attention for verification steps of up to 64 rows (FV_ATTN=legacy: off)
     int gemm_fix = 1;            // 128 / 256 tokens: separate reduction launch for QKV, O and down (FV_GEMM_FIX=0: off, 2: every GEMM)
     std::vector<hipEvent_t> pev;       // event pool for profiling
     std::vector<int> pev_phase;        // phase of each (start, stop) pair

@@ -18,6 +18,7 @@ struct IngestArgs {
     uint64_t* mask;          // [Tp][4]
     int32_t* pos;            // [Tp]
     float2* rope_cs;         // [Tp][half_d]  (cos, sin)
+    uint8_t* anc;            // [Tp][FV_CANON_DEPTH + 1]: node i's ancestor at depth d, for nodes no deeper than that (or null)
 };
 
 #ifndef FV_TS
@@ -41,8 +42,10 @@ static __global__ __launch_bounds__(256) void k_ingest(IngestArgs a) {
         int p = 0;
         if (i < a.T) {
             int j = i, guard = 0;
+            const bool by_depth = a.anc && depth[i] <= FV_CANON_DEPTH;
             while (j >= 0 && guard++ < FV_MAX_TREE) {   // host validated parent[j] < j; guard bounds the walk anyway
                 m[j >> 6] |= 1ull << (j & 63);
+                if (by_depth && depth[j] >= 0 && depth[j] <= FV_CANON_DEPTH) a.anc[i * (FV_CANON_DEPTH + 1) + depth[j]] = (uint8_t)j;
                 j = parent[j];
             }
             p = a.L + depth[i];
@@ -1017,6 +1020,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     }
     attn_body<EL, D>(a, item, part, smem);
 }
+
+#include "fv_attn_canon.hpp"
 
 // ============================================================================ argmax
 // Greedy choice per node: wavefront shuffle reduction on (value, index), lowest index on ties.

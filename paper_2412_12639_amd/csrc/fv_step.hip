@@ -79,6 +79,8 @@ int set_gemm_attrs_e() {
 }
 template <typename EL, int D>
 int set_gemm_attrs_d() {
+    HIPCHK(hipFuncSetAttribute((const void*)k_attn_canon<EL, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               FV_CANON_SMEM_BYTES(D, Tr<EL>::ESZ)));
     int rc = set_gemm_attrs_e<EL, D, EPI_QKV>();
     if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_RESID>();
     if (!rc) rc = set_gemm_attrs_e<EL, D, EPI_SWIGLU>();
@@ -94,6 +96,41 @@ static int attn_key_split(int items, int n_keys, int n_wg) {
     if (ks > 8) ks = 8;
     if (ks < 1) ks = 1;
     return ks;
+}
+
+// Step-independent attention (fv_attn_canon.hpp): taken by verification steps (one-token steps are
+// verification steps of a one-node tree) of up to 64 rows whose nodes are at most FV_CANON_DEPTH
+// deep, when the far parts fit the triple slots of the scratch in use.  Fills everything of `ca`
+// that does not change from layer to layer and returns true, or returns false (k_attn then).
+template <typename EL, int D>
+static bool plan_canon_attention(const fv_ctx* c, int T, int Tp, StepMode mode, CanonArgs& ca) {
+    if (!c->attn_canon || (mode != STEP_VERIFY && mode != STEP_VERIFY_SAMPLED) || Tp > 64) return false;
+    int maxdepth = 0;
+    for (int i = 0; i < T; ++i) maxdepth = std::max(maxdepth, (int)c->h_in[2 * FV_MAX_TREE + i]);
+    if (maxdepth > FV_CANON_DEPTH) return false;
+    const fv_cfg& cf = c->cfg;
+    const int L = c->cur_len;
+    const int pb = (L + maxdepth) >> 5;
+    const int nfb = pb > 0 ? pb - 1 : 0, np = canon_parts(nfb);
+    if (np > FV_CANON_MAX_PARTS || np + 1 > c->scr->aslots) return false;
+    memset(&ca, 0, sizeof(ca));
+    ca.Tp = Tp; ca.T = T; ca.L = L; ca.Hq = cf.n_q_heads; ca.Hkv = cf.n_kv_heads; ca.S_pad = c->lay.S_pad;
+    ca.scale = 1.f / std::sqrt((float)D);
+    ca.nfb = nfb; ca.np = np;
+    const int items = cf.n_q_heads * (Tp / 32);
+    int kw = 256 / items;
+    ca.kw = kw < 1 ? 1 : kw > 8 ? 8 : kw;
+    // parts to workgroups: heaviest first, each to the least loaded workgroup
+    int load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = np - 1; j >= 0; --j) {
+        int best = 0;
+        for (int w = 1; w < ca.kw; ++w) if (load[w] < load[best]) best = w;
+        ca.owner[j] = (unsigned char)best;
+        load[best] += canon_part_run(j) + 1;   // a run of blocks plus the part's merge
+    }
+    ca.pos = c->at<int32_t>(c->lay.off_pos); ca.anc = c->at<uint8_t>(c->lay.off_anc);
+    ca.part = c->scr->apart; ca.tickets = c->scr->atick;
+    return true;
 }
 
 // One pass of the decoder over T new rows whose tokens/parent/depth are in c->h_in.
@@ -117,6 +154,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         ia.tok_in = c->at<int32_t>(ly.off_stepin); ia.cap = FV_MAX_TREE; ia.T = T; ia.Tp = Tp; ia.L = L; ia.half_d = D / 2;
         ia.log2_base = std::log2((double)cf.rope_base);
         ia.mask = c->at<uint64_t>(ly.off_mask); ia.pos = c->at<int32_t>(ly.off_pos); ia.rope_cs = c->at<float2>(ly.off_rope);
+        ia.anc = c->at<uint8_t>(ly.off_anc);
         hipLaunchKernelGGL(k_ingest, dim3((Tp + 3) / 4), dim3(256), 0, st, ia);
         EmbedArgs ea;
         ea.table = c->at<void>(ly.off_embed); ea.tok = c->at<int32_t>(ly.off_stepin); ea.gain = c->gain(0);
@@ -145,6 +183,9 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         return ga;
     };
 
+    CanonArgs ca;
+    const bool canon = plan_canon_attention<EL, D>(c, T, Tp, mode, ca);
+
     for (int l = 0; l < cf.n_layers; ++l) {
         int rc;
         {   // q, k, v projections of the normalised input, rotary at pos = L + depth, K/V to cache slots L + i
@@ -155,7 +196,14 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, kind_of(GM_QKV));
             if (rc) return rc;
         }
-        {
+        if (canon) {
+            PhaseTimer pt(c, FV_PH_ATTN);
+            ca.q = c->at<uint4>(ly.off_q); ca.q_lo = c->at<uint4>(ly.off_qlo); ca.kc = (const uint4*)c->kc(l); ca.vc = (const uint4*)c->vc(l);
+            ca.out = c->at<void>(ly.off_attn);
+            hipLaunchKernelGGL((k_attn_canon<EL, D>), dim3(cf.n_q_heads * (Tp / 32) * ca.kw), dim3(256),
+                               FV_CANON_SMEM_BYTES(D, Tr<EL>::ESZ), st, ca);
+            HIPCHK(hipGetLastError());
+        } else {
             PhaseTimer pt(c, FV_PH_ATTN);
             AttnArgs aa;
             aa.q = c->at<uint4>(ly.off_q); aa.q_lo = c->at<uint4>(ly.off_qlo); aa.kc = (const uint4*)c->kc(l); aa.vc = (const uint4*)c->vc(l);
