@@ -181,6 +181,22 @@ int fv_verify_tree_noalloc(fv_ctx* ctx, const int32_t* tree_tokens, const int32_
                            const int32_t* depth, int32_t n_nodes,
                            int32_t* accepted_len, int32_t* accepted_tokens, int32_t* next_token);
 
+/* Step-invariant rows (paper, Abstract and section "Custom-Designed Decoding Tree": the output of
+ * drafting plus verification is exactly the target's own greedy output).  With this on, the logits,
+ * the K/V rows and the features of a node are bitwise the same whether the node is verified alone
+ * (a one-node tree per step, i.e. plain decoding) or as one node of any tree of up to 64 nodes and
+ * depth up to 32, so a decoding loop built on fv_verify_tree emits bit for bit what one-token steps
+ * emit, top-2 near-ties included.  Off (the default), a node's attention sums are grouped by the
+ * step's row count and by the cache slots its ancestors happen to occupy; rows then agree to
+ * rounding level only (the 2e-2 parity bar holds either way) and a near-tie can tip.  It applies to
+ * fv_verify_tree, fv_verify_tree_noalloc and fv_verify_tree_sampled; steps with more than 64 nodes
+ * or deeper nodes, and fv_prefill, compute the same thing in the default form.  Costs attention
+ * time (the last 33..64 positions of every node are summed per node in position order instead of
+ * through shared matrix tiles); fv_verify_tree_noalloc then also needs the step's far-key parts to
+ * fit its scratch (prefixes up to about 1300 tokens), else FV_E_SCRATCH_LIMIT.
+ * enabled: 0 or 1.  May be changed between steps. */
+int fv_set_step_invariant(fv_ctx* ctx, int32_t enabled);
+
 /* Reset the committed length and pending root (0 <= new_len <= current capacity use is
  * the caller's responsibility: slots below new_len must hold valid K/V).  Used to replay
  * the same step and to resume. */

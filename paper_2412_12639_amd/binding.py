@@ -79,6 +79,7 @@ def load_library():
         "fv_debug_read_activation": [vp, C.c_int32, C.c_int32, C.POINTER(C.c_float)],
         "fv_stream_read": [vp, C.c_int32, C.POINTER(C.c_float)],
         "fv_set_profiling": [vp, C.c_int32],
+        "fv_set_step_invariant": [vp, C.c_int32],
         "fv_get_phase_times": [vp, C.POINTER(C.c_float), i32p],
         "fv_last_step_ms": [vp, C.POINTER(C.c_float)],
         "fv_drafter_workspace_bytes": [C.POINTER(fv_cfg), C.POINTER(C.c_size_t)],
@@ -313,6 +314,10 @@ class FalconVerifier:
         self._chk(self.lib.fv_debug_read_activation(self.ctx, idx, n, out.ctypes.data_as(C.POINTER(C.c_float))),
                   "fv_debug_read_activation")
         return out
+
+    def set_step_invariant(self, on: bool):
+        """Rows bitwise independent of the step they are verified in (see fv_set_step_invariant)."""
+        self._chk(self.lib.fv_set_step_invariant(self.ctx, 1 if on else 0), "fv_set_step_invariant")
 
     # ---- measurement
     def set_profiling(self, on: bool):

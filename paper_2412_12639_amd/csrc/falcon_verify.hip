@@ -389,7 +389,7 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
         }
     }
     { const char* e = getenv("FV_GEMM_FIX"); c->gemm_fix = e ? atoi(e) : 1; }
-    { const char* e = getenv("FV_ATTN"); c->attn_canon = !(e && !strcmp(e, "legacy")); }
+    { const char* e = getenv("FV_ATTN"); c->attn_canon = e && !strcmp(e, "invariant"); }
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipHostMalloc((void**)&c->h_res, sizeof(FvResult), hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
@@ -684,6 +684,12 @@ int fv_stream_read(fv_ctx* c, int32_t passes, float* gbytes_per_s) {
     float ms = 0.f;
     HIPCHK(hipEventElapsedTime(&ms, c->ev0, c->ev1));
     *gbytes_per_s = (float)((double)bytes * passes / (ms * 1e-3) / 1e9);
+    return FV_OK;
+}
+
+int fv_set_step_invariant(fv_ctx* c, int32_t enabled) {
+    if (!c || (enabled != 0 && enabled != 1)) return FV_E_BAD_ARG;
+    c->attn_canon = enabled != 0;
     return FV_OK;
 }
 

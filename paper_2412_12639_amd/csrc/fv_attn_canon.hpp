@@ -66,6 +66,32 @@ __device__ __forceinline__ float canon_wave_sum(float v) {   // the same tree in
     return v;
 }
 
+// What a window job reads from global memory: requested one job ahead, so that its round trip is
+// hidden behind the staging of the rows (first job) or the previous job's arithmetic.
+template <int FPL> struct CanonJob { float q[FPL]; int p; int anc; };
+
+template <typename EL, int D>
+__device__ __forceinline__ CanonJob<D / 64> canon_job_load(const CanonArgs& a, int qh, int t, int lane) {
+    constexpr int E = Tr<EL>::E, VPR = D / E, FPL = D / 64;
+    CanonJob<FPL> jb;
+    jb.p = 0; jb.anc = 0;
+#pragma unroll
+    for (int i = 0; i < FPL; ++i) jb.q[i] = 0.f;
+    if (t < a.T) {
+#pragma unroll
+        for (int i = 0; i < FPL; ++i) {   // q = hi + lo, exact in fp32
+            const int f = lane * FPL + i;
+            const size_t e = ((size_t)(qh * VPR + f / E) * a.Tp + t) * E + f % E;
+            float qv = Tr<EL>::load(a.q, e);
+            if constexpr (E == 8) qv += Tr<EL>::load(a.q_lo, e);
+            jb.q[i] = qv;
+        }
+        jb.p = a.pos[t];
+        jb.anc = (lane <= FV_CANON_DEPTH) ? a.anc[t * (FV_CANON_DEPTH + 1) + lane] : 0;   // lane d: the ancestor at depth d
+    }
+    return jb;
+}
+
 // The window triples of nodes [n0, n1) of the item, one wavefront per node.
 template <typename EL, int D>
 __device__ __forceinline__ void canon_window(const CanonArgs& a, int qh, int kh, int tb, int n0, int n1, char* lds, float* slot) {
@@ -86,87 +112,127 @@ __device__ __forceinline__ void canon_window(const CanonArgs& a, int qh, int kh,
     const uint4* kslab = a.kc + (size_t)kh * slab_vecs;
     const uint4* vslab = a.vc + (size_t)kh * slab_vecs;
 
-    // ---- stage the rows: K row-major as stored per position, V transposed out of its operand order
-    for (int idx = tid; idx < NR * VPR; idx += 256) {
-        const int r = idx / VPR, c = idx % VPR, s = WS0 + r;
-        *(uint4*)(Kl + r * KS + c * 16) = kslab[((size_t)(s >> 5) * NF + (c >> 1)) * 64 + (s & 31) * 2 + (c & 1)];
-    }
-    const int pb0 = WS0 >> 5, pb1 = (a.L + a.T - 1) >> 5;
+    CanonJob<FPL> cur = canon_job_load<EL, D>(a, qh, tb * 32 + n0 + wave, lane);
+
+    // ---- stage the rows: K row-major as stored per position, V transposed out of its operand order.
+    // All requests go out before the first LDS write (a loop of load-then-store pairs pays one memory
+    // round trip per iteration: 14 of them made this kernel three times slower than k_attn).
+    constexpr int KIT = (FV_CANON_WIN_ROWS * VPR + 255) / 256;
     constexpr int VPB = DB * NQ * 64;      // vectors per key block
-    for (int idx = tid; idx < (pb1 - pb0 + 1) * VPB; idx += 256) {
-        const int pb = pb0 + idx / VPB, v = idx % VPB;
-        const int g = v & 1, f = (v >> 1) & 31, q = (v >> 6) % NQ, db = (v >> 6) / NQ;
-        const uint4 vec = vslab[(size_t)pb * VPB + v];
-        elem_t el[E];
-        __builtin_memcpy(el, &vec, 16);
+    constexpr int VIT = (4 * VPB + 255) / 256;   // the rows lie in at most four key blocks
+    const int pb0 = WS0 >> 5, pb1 = (a.L + a.T - 1) >> 5;
+    const int nkv = NR * VPR, nvv = (pb1 - pb0 + 1) * VPB;
+    uint4 kst[KIT], vst[VIT];
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int i = q * E + e;
-            const int r = pb * 32 + 8 * (i >> 2) + 4 * g + (i & 3) - WS0;
-            if (r >= 0 && r < NR) *(elem_t*)(Vl + r * VS + (db * 32 + f) * ESZ) = el[e];
+    for (int it = 0; it < KIT; ++it) {
+        const int idx = tid + it * 256;
+        const int r = idx / VPR, c = idx % VPR, sl_ = WS0 + r;
+        if (idx < nkv) kst[it] = kslab[((size_t)(sl_ >> 5) * NF + (c >> 1)) * 64 + (sl_ & 31) * 2 + (c & 1)];
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+        const int idx = tid + it * 256;
+        if (idx < nvv) vst[it] = vslab[(size_t)pb0 * VPB + idx];
+    }
+#pragma unroll
+    for (int it = 0; it < KIT; ++it) {
+        const int idx = tid + it * 256;
+        if (idx < nkv) *(uint4*)(Kl + (idx / VPR) * KS + (idx % VPR) * 16) = kst[it];
+    }
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+        const int idx = tid + it * 256;
+        if (idx < nvv) {
+            const int pb = pb0 + idx / VPB, v = idx % VPB;
+            const int g = v & 1, f = (v >> 1) & 31, q = (v >> 6) % NQ, db = (v >> 6) / NQ;
+            elem_t el[E];
+            __builtin_memcpy(el, &vst[it], 16);
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const int i = q * E + e;
+                const int r = pb * 32 + 8 * (i >> 2) + 4 * g + (i & 3) - WS0;
+                if (r >= 0 && r < NR) *(elem_t*)(Vl + r * VS + (db * 32 + f) * ESZ) = el[e];
+            }
         }
     }
     __syncthreads();
 
     for (int n = n0 + wave; n < n1; n += 4) {
         const int t = tb * 32 + n;
+        const CanonJob<FPL> jb = cur;
+        if (n + 4 < n1) cur = canon_job_load<EL, D>(a, qh, t + 4, lane);
         float m = -1e30f, l = 0.f, acc[FPL];
 #pragma unroll
         for (int i = 0; i < FPL; ++i) acc[i] = 0.f;
         if (t < a.T) {   // wavefront-uniform
-            // q = hi + lo, exact in fp32
 #pragma unroll
-            for (int i = 0; i < FPL; ++i) {
-                const int f = lane * FPL + i;
-                const size_t e = ((size_t)(qh * VPR + f / E) * a.Tp + t) * E + f % E;
-                float qv = Tr<EL>::load(a.q, e);
-                if constexpr (E == 8) qv += Tr<EL>::load(a.q_lo, e);
-                ql[f] = qv;
-            }
+            for (int i = 0; i < FPL; ++i) ql[lane * FPL + i] = jb.q[i];
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const int p = a.pos[t];
+            const int p = jb.p;
             const int pbk = p >> 5;
             const int ws = 32 * (pbk > 0 ? pbk - 1 : 0);
             const int nw = p - ws + 1;                 // window positions, 1 .. 64
             const bool valid = lane < nw;
-            int row = 0;
-            if (valid) {
-                const int pj = ws + lane;
-                const int s = pj < a.L ? pj : a.L + a.anc[t * (FV_CANON_DEPTH + 1) + (pj - a.L)];
-                row = s - WS0;
-            }
-            // score of this lane's position: features in ascending order, one fused multiply-add each
-            float sc = 0.f;
+            const int pj0 = ws + lane;
+            const int anc_j = __shfl(jb.anc, (pj0 - a.L) & 63);   // tree positions: the ancestor at depth pj - L
+            const int row = valid ? (pj0 < a.L ? pj0 : a.L + anc_j) - WS0 : 0;
+            // score of this lane's position: four interleaved sums over the features (feature f goes to sum f % 4,
+            // ascending), added as (s0 + s1) + (s2 + s3): a fixed order, and four times less waiting for the previous add
+            float s4[4] = {0.f, 0.f, 0.f, 0.f};
             const char* kr = Kl + row * KS;
 #pragma unroll 4
             for (int c = 0; c < VPR; ++c) {
                 const uint4 kv = *(const uint4*)(kr + c * 16);
                 elem_t ke[E];
                 __builtin_memcpy(ke, &kv, 16);
+                float qe[E];
+#pragma unroll
+                for (int e = 0; e < E; e += 4) {
+                    const float4 q4 = *(const float4*)(ql + c * E + e);   // the same address in every lane: a broadcast read
+                    qe[e] = q4.x; qe[e + 1] = q4.y; qe[e + 2] = q4.z; qe[e + 3] = q4.w;
+                }
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
                     float kf;
                     if constexpr (E == 8) kf = bf16_bits_to_f32(ke[e]); else kf = ke[e];
-                    sc = fmaf(ql[c * E + e], kf, sc);
+                    s4[e & 3] = fmaf(qe[e], kf, s4[e & 3]);
                 }
             }
+            float sc = (s4[0] + s4[1]) + (s4[2] + s4[3]);
             sc = valid ? sc * a.scale : -1e30f;
             m = canon_wave_max(sc);
-            const float pj = valid ? __expf(sc - m) : 0.f;
+            const float pj = valid ? __expf(sc - m) : 0.f;   // zero beyond the window: those lanes add nothing below
             l = canon_wave_sum(pj);
-            // output: positions in ascending order
-            for (int j = 0; j < nw; ++j) {
-                const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pj), j));
-                const int rj = __builtin_amdgcn_readlane(row, j);
-                const char* vr = Vl + rj * VS + lane * FPL * ESZ;
+            // output: positions in ascending order, eight rows requested at a time
+            for (int j0 = 0; j0 < nw; j0 += 8) {
+                float w[8];
+                const char* vr[8];
 #pragma unroll
-                for (int i = 0; i < FPL; ++i) {
-                    float vf;
-                    if constexpr (E == 8) vf = bf16_bits_to_f32(((const uint16_t*)vr)[i]); else vf = ((const float*)vr)[i];
-                    acc[i] = fmaf(w, vf, acc[i]);
+                for (int u = 0; u < 8; ++u) {
+                    const int j = (j0 + u) & 63;
+                    w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pj), j));
+                    vr[u] = Vl + __builtin_amdgcn_readlane(row, j) * VS + lane * FPL * ESZ;
                 }
+                float vf[8][FPL];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if constexpr (E == 8 && FPL == 2) {
+                        const uint32_t two = *(const uint32_t*)vr[u];
+                        vf[u][0] = __builtin_bit_cast(float, two << 16);
+                        vf[u][1] = __builtin_bit_cast(float, two & 0xffff0000u);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < FPL; ++i) {
+                            if constexpr (E == 8) vf[u][i] = bf16_bits_to_f32(((const uint16_t*)vr[u])[i]); else vf[u][i] = ((const float*)vr[u])[i];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+#pragma unroll
+                    for (int i = 0; i < FPL; ++i) acc[i] = fmaf(w[u], vf[u][i], acc[i]);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();   // ql is rewritten by the next node of this wavefront
@@ -200,6 +266,39 @@ __device__ __forceinline__ void attn_canon_body(const CanonArgs& a, int item, in
     const int t = tb * 32 + tl;
     float* slots = a.part + (size_t)item * (a.np + 1) * PF;
 
+    // Everything the far parts read from global memory before their first matrix product is requested
+    // now, ahead of the window, so that the kernel pays that round trip once: q, and the K and V tiles
+    // of the first block of this wavefront's first run.
+    int j_first = -1;
+    for (int j = a.np - 1; j >= 0; --j) if (a.owner[j] == k) j_first = j;
+    const bool mine = j_first >= 0;
+    uint4 qf[NF], qfl[SPLIT ? NF : 1];
+    uint4 kt0[NF], vt0[DB * NQ];
+    const size_t slab_vecs = (size_t)a.S_pad * D / E;
+    const uint4* kslab = a.kc + (size_t)kh * slab_vecs;
+    const uint4* vslab = a.vc + (size_t)kh * slab_vecs;
+    const int lidx = tl * 2 + g;
+    auto load_block = [&](uint4 (&kt)[NF], uint4 (&vt)[DB * NQ], int kb) {
+        const uint4* kp = kslab + (size_t)kb * NF * 64 + lidx;
+        const uint4* vp = vslab + (size_t)kb * DB * NQ * 64 + lidx;
+#pragma unroll
+        for (int fr = 0; fr < NF; ++fr) kt[fr] = kp[fr * 64];
+#pragma unroll
+        for (int jj = 0; jj < DB * NQ; ++jj) vt[jj] = vp[jj * 64];
+    };
+    int p_t = 0;
+    if (mine) {
+#pragma unroll
+        for (int fr = 0; fr < NF; ++fr) qf[fr] = a.q[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
+        if constexpr (SPLIT) {
+#pragma unroll
+            for (int fr = 0; fr < NF; ++fr) qfl[fr] = a.q_lo[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
+        }
+        p_t = (t < a.T) ? a.pos[t] : 0;
+        const int kb = canon_part_b0(j_first) + wave * canon_part_run(j_first);
+        if (kb < a.nfb) load_block(kt0, vt0, kb);
+    }
+
     canon_window<EL, D>(a, qh, kh, tb, 32 * k / a.kw, 32 * (k + 1) / a.kw, lds, slots + (size_t)a.np * PF);
     __syncthreads();   // the far parts reuse the window's LDS
 
@@ -209,24 +308,9 @@ __device__ __forceinline__ void attn_canon_body(const CanonArgs& a, int item, in
     float* sl = sm + 4 * 32;                       // [4][32] sums
     int* ticket_lds = (int*)(sl + 4 * 32);
 
-    bool mine = false;
-    for (int j = 0; j < a.np; ++j) mine |= a.owner[j] == k;
     if (mine) {
-        uint4 qf[NF], qfl[SPLIT ? NF : 1];
-#pragma unroll
-        for (int fr = 0; fr < NF; ++fr) qf[fr] = a.q[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
-        if constexpr (SPLIT) {
-#pragma unroll
-            for (int fr = 0; fr < NF; ++fr) qfl[fr] = a.q_lo[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
-        }
-        const int p_t = (t < a.T) ? a.pos[t] : 0;
         const int nfb_t = (t < a.T && (p_t >> 5) > 0) ? (p_t >> 5) - 1 : 0;   // this node's far blocks
-        const size_t slab_vecs = (size_t)a.S_pad * D / E;
-        const uint4* kslab = a.kc + (size_t)kh * slab_vecs;
-        const uint4* vslab = a.vc + (size_t)kh * slab_vecs;
-        const int lidx = tl * 2 + g;
-
-        for (int j = 0; j < a.np; ++j) {
+        for (int j = j_first; j < a.np; ++j) {
             if (a.owner[j] != k) continue;
             const int run = canon_part_run(j), kb0 = canon_part_b0(j) + wave * run;
             floatx16 o[DB];
@@ -237,13 +321,13 @@ __device__ __forceinline__ void attn_canon_body(const CanonArgs& a, int item, in
             float m_run = -1e30f, l_run = 0.f;
             for (int kb = kb0; kb < kb0 + run && kb < a.nfb; ++kb) {
                 uint4 kt[NF], vt[DB * NQ];
-                {
-                    const uint4* kp = kslab + (size_t)kb * NF * 64 + lidx;
-                    const uint4* vp = vslab + (size_t)kb * DB * NQ * 64 + lidx;
+                if (j == j_first && kb == kb0) {
 #pragma unroll
-                    for (int fr = 0; fr < NF; ++fr) kt[fr] = kp[fr * 64];
+                    for (int fr = 0; fr < NF; ++fr) kt[fr] = kt0[fr];
 #pragma unroll
-                    for (int jj = 0; jj < DB * NQ; ++jj) vt[jj] = vp[jj * 64];
+                    for (int jj = 0; jj < DB * NQ; ++jj) vt[jj] = vt0[jj];
+                } else {
+                    load_block(kt, vt, kb);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 floatx16 s, s1;
@@ -362,24 +446,31 @@ __device__ __forceinline__ void attn_canon_body(const CanonArgs& a, int item, in
     if (tid == 0) __hip_atomic_store(&a.tickets[item], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next use
     const int ns = a.np + 1;
     for (int db = wave; db < DB; db += 4) {
+        // slot order; the common reference is the largest of the slots' references.  Up to eight slots are requested
+        // in one go (the merge then costs one memory round trip); beyond that the references are read first.
         float Mx = -1e30f;
-        for (int c = 0; c < ns; ++c)
-            Mx = fmaxf(Mx, __hip_atomic_load(slots + (size_t)c * PF + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if (ns > 8)
+            for (int c = 0; c < ns; ++c)
+                Mx = fmaxf(Mx, __hip_atomic_load(slots + (size_t)c * PF + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         float accv[16], ltot = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) accv[i] = 0.f;
-        for (int c0 = 0; c0 < ns; c0 += 4) {   // slot order, four slots in flight
-            float mc[4], lc[4], v[4][16];
+        for (int c0 = 0; c0 < ns; c0 += 8) {
+            float mc[8], lc[8], v[8][16];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const float* cp = slots + (size_t)(c0 + u < ns ? c0 + u : 0) * PF;
                 mc[u] = __hip_atomic_load(cp + DB * 1024 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 lc[u] = __hip_atomic_load(cp + DB * 1024 + 32 + tl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) v[u][i] = __hip_atomic_load(cp + (db * 16 + i) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+            if (ns <= 8) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 8; ++u) if (u < ns) Mx = fmaxf(Mx, mc[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
                 if (c0 + u < ns) {   // wavefront-uniform
                     const float wc = __expf(mc[u] - Mx);
                     ltot += wc * lc[u];

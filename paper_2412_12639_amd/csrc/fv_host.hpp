@@ -99,7 +99,7 @@ struct fv_ctx {
     float last_ms = 0.f;
     bool profiling = false;
     int kind[GM_COUNT];       // GemmKind per matrix, used up to 64 tokens
-    bool attn_canon = true;      // step-independent attention for verification steps of up to 64 rows (FV_ATTN=legacy: off)
+    bool attn_canon = false;     // step-independent attention for verification steps of up to 64 rows (fv_set_step_invariant)
     int gemm_fix = 1;            // 128 / 256 tokens: separate reduction launch for QKV, O and down (FV_GEMM_FIX=0: off, 2: every GEMM)
     std::vector<hipEvent_t> pev;       // event pool for profiling
     std::vector<int> pev_phase;        // phase of each (start, stop) pair

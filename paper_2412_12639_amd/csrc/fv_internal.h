@@ -13,8 +13,7 @@
  *   FV_GEMM_FIX = 0           steps of more than 64 rows: let the last workgroup to arrive reduce a row
  *       group's partial tiles inside the GEMM launch (default: a second launch reduces them, one
  *       wavefront per tile, for the QKV, O and down projections).
- *   FV_ATTN = legacy          verification steps of up to 64 rows use the same attention kernel as every other step
- *       (key split by row count; a node's result then depends, at rounding level, on the step it is in).
+ *   FV_ATTN = invariant       contexts start with step-invariant rows switched on (fv_set_step_invariant(ctx, 1)).
  *   FV_DEBUG = 1              print the failing HIP call of an FV_E_HIP status to stderr.
  */
 #ifndef FV_INTERNAL_H

@@ -3,6 +3,7 @@
 #include "fv_host.hpp"
 #include "fv_kernels.hpp"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 

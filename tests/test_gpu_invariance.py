@@ -16,6 +16,7 @@ def _verifier(shape, weights, max_seq, max_tree=64):
     import paper_2412_12639_amd as m
     g = m.FalconVerifier(shape, max_seq=max_seq, max_tree=max_tree, device="cuda:0")
     g.init_weights(weights)
+    g.set_step_invariant(True)
     return g
 
 

@@ -27,9 +27,11 @@ def fvmod():
     return m
 
 
-def make_gpu(fvmod, shape, weights, max_seq, max_tree):
+def make_gpu(fvmod, shape, weights, max_seq, max_tree, invariant=False):
     g = fvmod.FalconVerifier(shape, max_seq=max_seq, max_tree=max_tree)
     g.init_weights(weights)
+    if invariant:
+        g.set_step_invariant(True)   # the step-invariant form of the attention, held to the same oracle
     return g
 
 
@@ -93,12 +95,13 @@ def test_prefill_logits_and_layer_intermediates(fvmod, name):
     ("tiny-bf16", 16, [4, 2, 1, 1], 4, 64),
     ("small-gqa", 64, [8, 4, 2, 2, 1, 1], 3, 70),
 ])
-def test_verify_planted_tree(fvmod, name, n, br, plant, L):
+@pytest.mark.parametrize("invariant", [False, True])
+def test_verify_planted_tree(fvmod, name, n, br, plant, L, invariant):
     s, w = SHAPES[name], weights_of(name)
     tol = H.tol_for(s)
-    say("verify", name, n, br, plant, L)
+    say("verify", name, n, br, plant, L, "step-invariant rows" if invariant else "")
     case = H.planted_case(s, w, L, n, br, plant, seed=0)
-    g = make_gpu(fvmod, s, w, max_seq=L + n + 8, max_tree=max(n, 64))
+    g = make_gpu(fvmod, s, w, max_seq=L + n + 8, max_tree=max(n, 64), invariant=invariant)
     root = g.prefill(case["prefix"])
     assert root == case["root"]
     got = g.verify_tree(case["tokens"], case["parent"], case["depth"])
@@ -429,9 +432,9 @@ def _wide_case(s, w, L, n_nodes, branching, plant, seed, tol, max_last_tokens=40
                 prefill_last=rows[0], hidden=o.last_hidden.copy(), clear=clear, plant=plant)
 
 
-def _run_wide(fvmod, s, w, case, L, T, tol, max_tree=256):
+def _run_wide(fvmod, s, w, case, L, T, tol, max_tree=256, invariant=False):
     """Device step on a _wide_case instance, in the launch configuration bench.py times (max_tree 256)."""
-    g = make_gpu(fvmod, s, w, max_seq=L + max_tree + 8, max_tree=max_tree)
+    g = make_gpu(fvmod, s, w, max_seq=L + max_tree + 8, max_tree=max_tree, invariant=invariant)
     groot = g.prefill(case["prefix"])
     pl = case["prefill_last"]
     if fo.top2_margin(pl) > tol * np.max(np.abs(pl)):
@@ -462,12 +465,14 @@ def test_benchmark_widths_two_layers_elementwise(fvmod, name, L, T, br, plant):
     branching = fi.random_branching(T, T) if br == "random" else br
     case = _wide_case(s, w, L, T, branching, plant, seed=T, tol=tol)
     assert case["clear"], "no tree with clear deciding margins in 12 draws"
-    g, got, ec = _run_wide(fvmod, s, w, case, L, T, tol)
-    e = H.check_step(g, case, got, tol, L=L)
-    say("logits err", e, "(bar 2e-2); prompt cache err", ec, "; accepted", got[0])
-    assert got[0] == plant
-    H.check_cache(g, case["oracle"], s, L + plant + 1, tol)
-    g.close()
+    # steps of up to 64 nodes also in the step-invariant form of the attention (same oracle, same bars)
+    for invariant in ([False, True] if T <= 64 else [False]):
+        g, got, ec = _run_wide(fvmod, s, w, case, L, T, tol, invariant=invariant)
+        e = H.check_step(g, case, got, tol, L=L)
+        say("step-invariant rows:" if invariant else "default:", "logits err", e, "(bar 2e-2); prompt cache err", ec, "; accepted", got[0])
+        assert got[0] == plant
+        H.check_cache(g, case["oracle"], s, L + plant + 1, tol)
+        g.close()
 
 
 _DEEP = {}

@@ -15,8 +15,9 @@ def _tree(seed, n, vocab, root):
     return fill_tokens(seed, parent, vocab, root), parent, depth
 
 
+@pytest.mark.parametrize("invariant", [False, True])
 @pytest.mark.parametrize("name", ["small-gqa", "small-gqa-f32", "7b-L2"])
-def test_noalloc_entry_point_equals_the_arena_one(name):
+def test_noalloc_entry_point_equals_the_arena_one(name, invariant):
     import torch
     assert torch.cuda.is_available(), "needs the GPU"
     import paper_2412_12639_amd as m
@@ -26,6 +27,7 @@ def test_noalloc_entry_point_equals_the_arena_one(name):
     L = 150
     g = m.FalconVerifier(s, max_seq=L + 80, max_tree=64)
     g.init_weights(w)
+    g.set_step_invariant(invariant)   # the attention's far-key parts and window live in the static array too
     root = g.prefill(fi.gen_prefix(9, L, s.vocab))
     for n in (61, 19):    # two calls in a row on the shared static array, the second one smaller
         tok, parent, depth = _tree(n, n, s.vocab, root)
@@ -63,4 +65,23 @@ def test_noalloc_entry_point_refuses_what_exceeds_its_scratch():
     assert ei.value.status == -11 and g.state() == (40, root)
     a, acc, nxt = g.verify_tree(tok[:1], parent[:1], depth[:1], noalloc=True)   # and still works afterwards
     assert a == 0 and g.state() == (41, nxt)
+    g.close()
+
+
+def test_noalloc_entry_point_refuses_a_prefix_whose_far_key_parts_exceed_its_slots():
+    """With step-invariant rows on, the far keys of a step are cut into parts at fixed positions, one slot each;
+    the static array holds eight slots per item, which a prefix of 1500 tokens exceeds."""
+    import paper_2412_12639_amd as m
+    s = fi.SHAPES["small-gqa"]
+    L = 1500
+    g = m.FalconVerifier(s, max_seq=L + 80, max_tree=64)
+    g.init_weights(fi.gen_weights(s, seed=0))
+    g.set_step_invariant(True)
+    root = g.prefill(fi.gen_prefix(9, L, s.vocab))
+    tok, parent, depth = _tree(3, 20, s.vocab, root)
+    with pytest.raises(m.FvError) as ei:
+        g.verify_tree(tok, parent, depth, noalloc=True)
+    assert ei.value.status == -11 and g.state() == (L, root)
+    a, acc, nxt = g.verify_tree(tok, parent, depth)   # the arena's scratch takes it
+    assert g.state() == (L + a + 1, nxt)
     g.close()
