@@ -435,6 +435,24 @@ def main():
                                   "note": "algorithmic K/V bytes over the per-launch HIP-event time of k_attn (profiling pass)"}
     if args.loop_tokens > 0:
         out["decode_loop"] = decode_loop(fi, gpu, shape, L, root, T, branching, args.loop_tokens, args.loop_p, args.seed)
+        # The same loop with step-invariant rows (fv_set_step_invariant): a node's logits are then bitwise the same in a
+        # one-token step and in a tree step, so the two decodings must agree token for token, near-ties included.
+        gpu.set_step_invariant(True)
+        dli = decode_loop(fi, gpu, shape, L, root, T, branching, args.loop_tokens, args.loop_p, args.seed)
+        assert dli["near_tie_disagreements_with_single_token_decoding"] == 0, \
+            "step-invariant rows are on, yet tree verification and one-token decoding emitted different tokens"
+        inv_ms = []
+        for _ in range(30):
+            gpu.rollback(L, root)
+            gpu.verify_tree(tokens, parent, depth)
+            inv_ms.append(gpu.last_step_ms())
+        gpu.rollback(L, root)
+        gpu.set_step_invariant(False)
+        dli["step_ms_device"] = float(np.median(inv_ms))
+        dli["nodes_per_s_device"] = T / float(np.median(inv_ms)) * 1e3
+        dli["note"] = ("fv_set_step_invariant(ctx, 1): attention sums follow the sequence positions, so the loop is lossless bit for "
+                       "bit; the headline value above is measured with the default form (rows equal up to rounding)")
+        out["decode_loop_step_invariant"] = dli
     if args.draft_k > 0:
         out["draft_phase"] = draft_phase(fi, m, gpu, shape, L, args.draft_k, args.draft_new, T, branching_draft, args.draft_reps, args.seed,
                                          gpu_weights=weights, cpu_too=args.cpu_layers != 0)

@@ -20,9 +20,10 @@
 //    only.  A block at or beyond a node's own nfb is invisible to it as a whole and contributes
 //    exact zeros, so a step that holds deeper nodes (more parts) changes nothing for this one.
 //  * WINDOW keys, positions [32 * nfb, p]: at most 64, one per lane, in position order whatever
-//    slots they occupy (prefix slots, then the node's ancestors by depth).  Scores, softmax and the
-//    weighted sum of V rows are plain fp32 vector arithmetic in a fixed order, from K/V rows staged
-//    in LDS; the result is one more triple in the slot after the last part.
+//    slots they occupy (prefix slots, then the node's ancestors by depth).  Their scores come from
+//    shared matrix tiles (a score does not depend on its key's slot); the softmax denominator and
+//    the weighted sum of V rows are fp32 vector arithmetic per node in a fixed order (see
+//    canon_window); the result is one more triple in the slot after the last part.
 //  * The last workgroup of an item to arrive merges the slots in slot order.
 //
 // The matrix cores see the far keys exactly as in k_attn (K and V tiles straight from the cache
@@ -48,44 +49,53 @@ struct CanonArgs {
     int* tickets;            // [item], zero on entry, left zero
 };
 
-// LDS: the window's rows (K rows padded by 16 bytes so that lanes reading different rows hit different
-// banks) and one q vector per wavefront; the far parts' merge area reuses the same bytes afterwards.
-#define FV_CANON_WIN_ROWS 128
-#define FV_CANON_WIN_BYTES(D, ESZ) (FV_CANON_WIN_ROWS * (2 * (D) * (ESZ) + 16) + 4 * (D) * 4)
+// LDS of the window: the scores of every (node, window slot) pair as fp32 [32 nodes][FV_CANON_SROW]
+// (an odd row length: the lanes of a score tile write one node each), and the V tiles of the
+// window's key blocks in the cache's own order, every 16-byte vector at a stride of 24 bytes so
+// that lanes reading one position of 64 different features hit different banks.  The far parts'
+// merge area reuses the same bytes afterwards.
+#define FV_CANON_WIN_BLOCKS 4    // key blocks the windows of one step can touch: L/32 - 1 .. (L + 63)/32
+#define FV_CANON_SROW (FV_CANON_WIN_BLOCKS * 32 + 1)
+#define FV_CANON_VSTRIDE 24
+#define FV_CANON_WIN_BYTES(D, ESZ) \
+    (32 * FV_CANON_SROW * 4 + FV_CANON_WIN_BLOCKS * ((D) / 32) * (ESZ) * 64 * FV_CANON_VSTRIDE)   /* NQ = 32 / (2E) = ESZ */
 #define FV_CANON_SMEM_BYTES(D, ESZ) \
     (FV_CANON_WIN_BYTES(D, ESZ) > FV_ATTN_SMEM_FLOATS(D) * 4 ? FV_CANON_WIN_BYTES(D, ESZ) : FV_ATTN_SMEM_FLOATS(D) * 4)
 
-__device__ __forceinline__ float canon_wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+// Wavefront-wide maximum and sum through the cross-lane data path (no LDS round trips): four steps
+// inside each row of 16 lanes, then row 0 into 1 and 2 into 3, then the lower half into the upper;
+// lane 63 holds the result.  One fixed tree: the sum of a window is the same bits in every step.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ float canon_dpp(float identity, float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity), __builtin_bit_cast(int, v),
+                                                                 CTRL, ROWS, 0xf, false));
 }
-__device__ __forceinline__ float canon_wave_sum(float v) {   // the same tree in every lane: all lanes end with the same bits
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+__device__ __forceinline__ float canon_wave_max(float v) {
+    v = fmaxf(v, canon_dpp<0xB1, 0xf>(-1e30f, v));    // quad_perm [1,0,3,2]
+    v = fmaxf(v, canon_dpp<0x4E, 0xf>(-1e30f, v));    // quad_perm [2,3,0,1]
+    v = fmaxf(v, canon_dpp<0x141, 0xf>(-1e30f, v));   // row_half_mirror
+    v = fmaxf(v, canon_dpp<0x140, 0xf>(-1e30f, v));   // row_mirror
+    v = fmaxf(v, canon_dpp<0x142, 0xa>(-1e30f, v));   // row_bcast 15 into rows 1 and 3
+    v = fmaxf(v, canon_dpp<0x143, 0xc>(-1e30f, v));   // row_bcast 31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+__device__ __forceinline__ float canon_wave_sum(float v) {
+    v += canon_dpp<0xB1, 0xf>(0.f, v);
+    v += canon_dpp<0x4E, 0xf>(0.f, v);
+    v += canon_dpp<0x141, 0xf>(0.f, v);
+    v += canon_dpp<0x140, 0xf>(0.f, v);
+    v += canon_dpp<0x142, 0xa>(0.f, v);
+    v += canon_dpp<0x143, 0xc>(0.f, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // What a window job reads from global memory: requested one job ahead, so that its round trip is
-// hidden behind the staging of the rows (first job) or the previous job's arithmetic.
-template <int FPL> struct CanonJob { float q[FPL]; int p; int anc; };
-
-template <typename EL, int D>
-__device__ __forceinline__ CanonJob<D / 64> canon_job_load(const CanonArgs& a, int qh, int t, int lane) {
-    constexpr int E = Tr<EL>::E, VPR = D / E, FPL = D / 64;
-    CanonJob<FPL> jb;
+// hidden behind the score tiles (first job) or the previous job's arithmetic.
+struct CanonJob { int p; int anc; };
+__device__ __forceinline__ CanonJob canon_job_load(const CanonArgs& a, int t, int lane) {
+    CanonJob jb;
     jb.p = 0; jb.anc = 0;
-#pragma unroll
-    for (int i = 0; i < FPL; ++i) jb.q[i] = 0.f;
     if (t < a.T) {
-#pragma unroll
-        for (int i = 0; i < FPL; ++i) {   // q = hi + lo, exact in fp32
-            const int f = lane * FPL + i;
-            const size_t e = ((size_t)(qh * VPR + f / E) * a.Tp + t) * E + f % E;
-            float qv = Tr<EL>::load(a.q, e);
-            if constexpr (E == 8) qv += Tr<EL>::load(a.q_lo, e);
-            jb.q[i] = qv;
-        }
         jb.p = a.pos[t];
         jb.anc = (lane <= FV_CANON_DEPTH) ? a.anc[t * (FV_CANON_DEPTH + 1) + lane] : 0;   // lane d: the ancestor at depth d
     }
@@ -93,83 +103,89 @@ __device__ __forceinline__ CanonJob<D / 64> canon_job_load(const CanonArgs& a, i
 }
 
 // The window triples of nodes [n0, n1) of the item, one wavefront per node.
-template <typename EL, int D>
-__device__ __forceinline__ void canon_window(const CanonArgs& a, int qh, int kh, int tb, int n0, int n1, char* lds, float* slot) {
+//
+// Scores do not care where a key sits: score(key, node) is one dot product over the features, the same bits in
+// whatever tile row the key's slot puts it.  So the scores of all 32 nodes against every slot of the window's key
+// blocks come from shared matrix tiles exactly as for the far keys (qf, qfl: this lane's q operand, hi and lo), and go
+// to LDS.  What has to follow the positions is the order of the sums: the softmax denominator and the weighted sum of V
+// rows, done per node by one wavefront -- lane j takes the node's j-th window position (looking its slot up: prefix
+// slots, then ancestors by depth), the denominator is one fixed tree over the lanes, and the output adds the positions
+// in ascending order, each lane for D/64 features, reading V straight from the staged tiles.
+template <typename EL, int D, int NFQ>
+__device__ __forceinline__ void canon_window(const CanonArgs& a, const uint4 (&qf)[NFQ], const uint4 (&qfl)[NFQ], int kh, int tb,
+                                             int n0, int n1, char* lds, float* slot) {
     constexpr int E = Tr<EL>::E, ESZ = Tr<EL>::ESZ;
     constexpr int NF = D / (2 * E), NQ = 32 / (2 * E), DB = D / 32;
-    constexpr int VPR = D / E;             // 16-byte vectors per row
-    constexpr int KS = D * ESZ + 16, VS = D * ESZ;
-    constexpr int FPL = D / 64;            // output features per lane
-    typedef typename Tr<EL>::elem_t elem_t;
+    constexpr int FPL = D / 64;            // output features per lane: lane, lane + 64
+    constexpr bool SPLIT = (E == 8);
+    constexpr int VPB = DB * NQ * 64;      // V vectors per key block
+    constexpr int VIT = (FV_CANON_WIN_BLOCKS * VPB + 255) / 256;
+    constexpr int VST = FV_CANON_VSTRIDE;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    char* Kl = lds;
-    char* Vl = Kl + FV_CANON_WIN_ROWS * KS;
-    float* ql = (float*)(Vl + FV_CANON_WIN_ROWS * VS) + wave * D;
+    const int tl = lane & 31, g = lane >> 5;
+    float* Sl = (float*)lds;
+    char* Vl = lds + 32 * FV_CANON_SROW * 4;
     const int lb = a.L >> 5;
-    const int WS0 = 32 * (lb > 0 ? lb - 1 : 0);      // first slot any row's window can start at
-    const int NR = a.L + a.T - WS0;                  // staged rows: slots WS0 .. L + T - 1
+    const int pb0 = lb > 0 ? lb - 1 : 0, pb1 = (a.L + a.T - 1) >> 5;   // key blocks the windows touch (at most four)
+    const int WS0 = 32 * pb0;
     const size_t slab_vecs = (size_t)a.S_pad * D / E;
     const uint4* kslab = a.kc + (size_t)kh * slab_vecs;
     const uint4* vslab = a.vc + (size_t)kh * slab_vecs;
 
-    CanonJob<FPL> cur = canon_job_load<EL, D>(a, qh, tb * 32 + n0 + wave, lane);
-
-    // ---- stage the rows: K row-major as stored per position, V transposed out of its operand order.
-    // All requests go out before the first LDS write (a loop of load-then-store pairs pays one memory
-    // round trip per iteration: 14 of them made this kernel three times slower than k_attn).
-    constexpr int KIT = (FV_CANON_WIN_ROWS * VPR + 255) / 256;
-    constexpr int VPB = DB * NQ * 64;      // vectors per key block
-    constexpr int VIT = (4 * VPB + 255) / 256;   // the rows lie in at most four key blocks
-    const int pb0 = WS0 >> 5, pb1 = (a.L + a.T - 1) >> 5;
-    const int nkv = NR * VPR, nvv = (pb1 - pb0 + 1) * VPB;
-    uint4 kst[KIT], vst[VIT];
+    // ---- requests: the K tiles of this wavefront's window block, the V tiles of all window blocks, the first job's data
+    const int kbw = pb0 + wave;
+    uint4 kt[NF];
+    if (kbw <= pb1) {
+        const uint4* kp = kslab + (size_t)kbw * NF * 64 + tl * 2 + g;
 #pragma unroll
-    for (int it = 0; it < KIT; ++it) {
-        const int idx = tid + it * 256;
-        const int r = idx / VPR, c = idx % VPR, sl_ = WS0 + r;
-        if (idx < nkv) kst[it] = kslab[((size_t)(sl_ >> 5) * NF + (c >> 1)) * 64 + (sl_ & 31) * 2 + (c & 1)];
+        for (int fr = 0; fr < NF; ++fr) kt[fr] = kp[fr * 64];
     }
+    const int nvv = (pb1 - pb0 + 1) * VPB;
+    uint4 vst[VIT];
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
         const int idx = tid + it * 256;
         if (idx < nvv) vst[it] = vslab[(size_t)pb0 * VPB + idx];
     }
+    CanonJob cur = canon_job_load(a, tb * 32 + n0 + wave, lane);
+
+    // ---- score tile of this wavefront's block: keys x nodes, to LDS as [node][slot - WS0]
+    if (kbw <= pb1) {
+        floatx16 s, s1;
 #pragma unroll
-    for (int it = 0; it < KIT; ++it) {
-        const int idx = tid + it * 256;
-        if (idx < nkv) *(uint4*)(Kl + (idx / VPR) * KS + (idx % VPR) * 16) = kst[it];
+        for (int i = 0; i < 16; ++i) { s[i] = 0.f; s1[i] = 0.f; }
+#pragma unroll
+        for (int fr = 0; fr < NF; fr += 2) {
+            s = Tr<EL>::mma(kt[fr], qf[fr], s);
+            s1 = Tr<EL>::mma(kt[fr + 1], qf[fr + 1], s1);
+            if constexpr (SPLIT) {
+                s = Tr<EL>::mma(kt[fr], qfl[fr], s);
+                s1 = Tr<EL>::mma(kt[fr + 1], qfl[fr + 1], s1);
+            }
+        }
+        float* sp = Sl + tl * FV_CANON_SROW + (kbw - pb0) * 32 + 4 * g;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sp[8 * (i >> 2) + (i & 3)] = (s[i] + s1[i]) * a.scale;
     }
 #pragma unroll
     for (int it = 0; it < VIT; ++it) {
         const int idx = tid + it * 256;
         if (idx < nvv) {
-            const int pb = pb0 + idx / VPB, v = idx % VPB;
-            const int g = v & 1, f = (v >> 1) & 31, q = (v >> 6) % NQ, db = (v >> 6) / NQ;
-            elem_t el[E];
-            __builtin_memcpy(el, &vst[it], 16);
-#pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const int i = q * E + e;
-                const int r = pb * 32 + 8 * (i >> 2) + 4 * g + (i & 3) - WS0;
-                if (r >= 0 && r < NR) *(elem_t*)(Vl + r * VS + (db * 32 + f) * ESZ) = el[e];
-            }
+            uint64_t* d = (uint64_t*)(Vl + (size_t)idx * VST);
+            d[0] = (uint64_t)vst[it].x | ((uint64_t)vst[it].y << 32);
+            d[1] = (uint64_t)vst[it].z | ((uint64_t)vst[it].w << 32);
         }
     }
     __syncthreads();
 
     for (int n = n0 + wave; n < n1; n += 4) {
         const int t = tb * 32 + n;
-        const CanonJob<FPL> jb = cur;
-        if (n + 4 < n1) cur = canon_job_load<EL, D>(a, qh, t + 4, lane);
+        const CanonJob jb = cur;
+        if (n + 4 < n1) cur = canon_job_load(a, t + 4, lane);
         float m = -1e30f, l = 0.f, acc[FPL];
 #pragma unroll
         for (int i = 0; i < FPL; ++i) acc[i] = 0.f;
         if (t < a.T) {   // wavefront-uniform
-#pragma unroll
-            for (int i = 0; i < FPL; ++i) ql[lane * FPL + i] = jb.q[i];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             const int p = jb.p;
             const int pbk = p >> 5;
             const int ws = 32 * (pbk > 0 ? pbk - 1 : 0);
@@ -177,56 +193,28 @@ __device__ __forceinline__ void canon_window(const CanonArgs& a, int qh, int kh,
             const bool valid = lane < nw;
             const int pj0 = ws + lane;
             const int anc_j = __shfl(jb.anc, (pj0 - a.L) & 63);   // tree positions: the ancestor at depth pj - L
-            const int row = valid ? (pj0 < a.L ? pj0 : a.L + anc_j) - WS0 : 0;
-            // score of this lane's position: four interleaved sums over the features (feature f goes to sum f % 4,
-            // ascending), added as (s0 + s1) + (s2 + s3): a fixed order, and four times less waiting for the previous add
-            float s4[4] = {0.f, 0.f, 0.f, 0.f};
-            const char* kr = Kl + row * KS;
-#pragma unroll 4
-            for (int c = 0; c < VPR; ++c) {
-                const uint4 kv = *(const uint4*)(kr + c * 16);
-                elem_t ke[E];
-                __builtin_memcpy(ke, &kv, 16);
-                float qe[E];
-#pragma unroll
-                for (int e = 0; e < E; e += 4) {
-                    const float4 q4 = *(const float4*)(ql + c * E + e);   // the same address in every lane: a broadcast read
-                    qe[e] = q4.x; qe[e + 1] = q4.y; qe[e + 2] = q4.z; qe[e + 3] = q4.w;
-                }
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    float kf;
-                    if constexpr (E == 8) kf = bf16_bits_to_f32(ke[e]); else kf = ke[e];
-                    s4[e & 3] = fmaf(qe[e], kf, s4[e & 3]);
-                }
-            }
-            float sc = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-            sc = valid ? sc * a.scale : -1e30f;
+            const int sj = valid ? (pj0 < a.L ? pj0 : a.L + anc_j) : WS0;   // this lane's slot
+            const float sc = valid ? Sl[n * FV_CANON_SROW + (sj - WS0)] : -1e30f;
             m = canon_wave_max(sc);
             const float pj = valid ? __expf(sc - m) : 0.f;   // zero beyond the window: those lanes add nothing below
             l = canon_wave_sum(pj);
-            // output: positions in ascending order, eight rows requested at a time
+            // byte offset of this lane's position inside the staged V tiles, for feature 0 of the block of 32 features:
+            // vector ((db * NQ + q) * 32 + f) * 2 + g of the key block, element e
+            const int pp = sj & 31, ii = 4 * (pp >> 3) + (pp & 3);
+            const int voff = ((((sj >> 5) - pb0) * VPB + (ii / E) * 64 + ((pp >> 2) & 1)) * VST) + (ii % E) * ESZ;
+            const char* vl = Vl + (((lane >> 5) * NQ * 64) + (lane & 31) * 2) * VST;   // feature `lane`: block lane / 32, row lane % 32
+            // output: positions in ascending order, eight of them requested at a time
             for (int j0 = 0; j0 < nw; j0 += 8) {
-                float w[8];
-                const char* vr[8];
+                float w[8], vf[8][FPL];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int j = (j0 + u) & 63;
                     w[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pj), j));
-                    vr[u] = Vl + __builtin_amdgcn_readlane(row, j) * VS + lane * FPL * ESZ;
-                }
-                float vf[8][FPL];
+                    const char* vr = vl + __builtin_amdgcn_readlane(voff, j);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    if constexpr (E == 8 && FPL == 2) {
-                        const uint32_t two = *(const uint32_t*)vr[u];
-                        vf[u][0] = __builtin_bit_cast(float, two << 16);
-                        vf[u][1] = __builtin_bit_cast(float, two & 0xffff0000u);
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < FPL; ++i) {
-                            if constexpr (E == 8) vf[u][i] = bf16_bits_to_f32(((const uint16_t*)vr[u])[i]); else vf[u][i] = ((const float*)vr[u])[i];
-                        }
+                    for (int i = 0; i < FPL; ++i) {   // feature lane + 64 i: two blocks of 32 features further on
+                        const char* ve = vr + i * (2 * NQ * 64 * VST);
+                        if constexpr (E == 8) vf[u][i] = bf16_bits_to_f32(*(const uint16_t*)ve); else vf[u][i] = *(const float*)ve;
                     }
                 }
 #pragma unroll
@@ -234,15 +222,13 @@ __device__ __forceinline__ void canon_window(const CanonArgs& a, int qh, int kh,
 #pragma unroll
                     for (int i = 0; i < FPL; ++i) acc[i] = fmaf(w[u], vf[u][i], acc[i]);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();   // ql is rewritten by the next node of this wavefront
         }
         // the triple, in the layout of the far parts' triples (accumulator order of the 32x32 tiles)
 #pragma unroll
         for (int i = 0; i < FPL; ++i) {
-            const int f = lane * FPL + i, fm = f & 31;
-            const int reg = 4 * (fm >> 3) + (fm & 3), g = (fm >> 2) & 1;
-            __hip_atomic_store(slot + ((f >> 5) * 16 + reg) * 64 + g * 32 + n, acc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int f = lane + 64 * i, fm = f & 31;
+            const int reg = 4 * (fm >> 3) + (fm & 3), gg = (fm >> 2) & 1;
+            __hip_atomic_store(slot + ((f >> 5) * 16 + reg) * 64 + gg * 32 + n, acc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (lane == 0) {
             __hip_atomic_store(slot + DB * 1024 + n, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -272,7 +258,7 @@ __device__ __forceinline__ void attn_canon_body(const CanonArgs& a, int item, in
     int j_first = -1;
     for (int j = a.np - 1; j >= 0; --j) if (a.owner[j] == k) j_first = j;
     const bool mine = j_first >= 0;
-    uint4 qf[NF], qfl[SPLIT ? NF : 1];
+    uint4 qf[NF], qfl[NF];   // (qfl is not used by fp32 builds)
     uint4 kt0[NF], vt0[DB * NQ];
     const size_t slab_vecs = (size_t)a.S_pad * D / E;
     const uint4* kslab = a.kc + (size_t)kh * slab_vecs;
@@ -287,19 +273,20 @@ __device__ __forceinline__ void attn_canon_body(const CanonArgs& a, int item, in
         for (int jj = 0; jj < DB * NQ; ++jj) vt[jj] = vp[jj * 64];
     };
     int p_t = 0;
+    int pre_kb = -1;   // the key block whose tiles kt0, vt0 hold
+#pragma unroll
+    for (int fr = 0; fr < NF; ++fr) qf[fr] = a.q[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
+    if constexpr (SPLIT) {
+#pragma unroll
+        for (int fr = 0; fr < NF; ++fr) qfl[fr] = a.q_lo[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
+    }
     if (mine) {
-#pragma unroll
-        for (int fr = 0; fr < NF; ++fr) qf[fr] = a.q[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
-        if constexpr (SPLIT) {
-#pragma unroll
-            for (int fr = 0; fr < NF; ++fr) qfl[fr] = a.q_lo[((size_t)(qh * (D / E) + 2 * fr + g)) * a.Tp + t];
-        }
         p_t = (t < a.T) ? a.pos[t] : 0;
         const int kb = canon_part_b0(j_first) + wave * canon_part_run(j_first);
-        if (kb < a.nfb) load_block(kt0, vt0, kb);
+        if (kb < a.nfb) { load_block(kt0, vt0, kb); pre_kb = kb; }
     }
 
-    canon_window<EL, D>(a, qh, kh, tb, 32 * k / a.kw, 32 * (k + 1) / a.kw, lds, slots + (size_t)a.np * PF);
+    canon_window<EL, D, NF>(a, qf, qfl, kh, tb, 32 * k / a.kw, 32 * (k + 1) / a.kw, lds, slots + (size_t)a.np * PF);
     __syncthreads();   // the far parts reuse the window's LDS
 
     float* smem = (float*)lds;
@@ -321,7 +308,7 @@ __device__ __forceinline__ void attn_canon_body(const CanonArgs& a, int item, in
             float m_run = -1e30f, l_run = 0.f;
             for (int kb = kb0; kb < kb0 + run && kb < a.nfb; ++kb) {
                 uint4 kt[NF], vt[DB * NQ];
-                if (j == j_first && kb == kb0) {
+                if (pre_kb == kb) {   // requested ahead of the window
 #pragma unroll
                     for (int fr = 0; fr < NF; ++fr) kt[fr] = kt0[fr];
 #pragma unroll
