@@ -46,5 +46,21 @@ def build(force: bool = True, verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+def build_probe(verbose: bool = False):
+    """The stand-alone GEMM timing aid (probe/fv_gemm_probe.hip): plain, with per-wavefront time stamps, and with the
+    activation and/or weight requests taken out of the streaming loop."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    src = os.path.join(HERE, "probe", "fv_gemm_probe.hip")
+    variants = [("", []), ("_stamps", ["-DFV_PROBE_STAMPS"]), ("_no_x", ["-DFV_PROBE_NO_X"]), ("_no_w", ["-DFV_PROBE_NO_W"]),
+                ("_no_loads", ["-DFV_PROBE_NO_X", "-DFV_PROBE_NO_W"]), ("_no_loads_stamps", ["-DFV_PROBE_NO_X", "-DFV_PROBE_NO_W", "-DFV_PROBE_STAMPS"])]
+    outs = [(os.path.join(HERE, "probe", "fv_gemm_probe" + suffix), defs) for suffix, defs in variants]
+    flags = [f for f in FLAGS if f != "-fPIC"]
+    with ThreadPoolExecutor(min(len(outs), os.cpu_count() or 1)) as ex:
+        list(ex.map(lambda o: _run([hipcc, *flags, *o[1], src, "-o", o[0]], verbose), outs))
+    return [o[0] for o in outs]
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose="-v" in sys.argv))
+    if "probe" in sys.argv:
+        print(build_probe(verbose="-v" in sys.argv))

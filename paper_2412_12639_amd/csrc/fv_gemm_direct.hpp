@@ -163,6 +163,9 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     // offsets stay instruction immediates) but one address for all lanes: a single cache-line
     // request per instruction rather than 1 KiB, and products that add nothing.
     auto load_w = [&](uint4 (&dst)[FV_FRAGS]) {
+#ifdef FV_PROBE_NO_W
+        return;
+#endif
         const bool live = rq.j < rq.n;
         const uint4* p = live ? rq.wp : zeros;
         // tile order inside a stage: paired: (strip r, frag f) at r*4 + f; one strip: frags 0-3, then frags 4-7 one
@@ -171,6 +174,9 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         for (int i = 0; i < FV_FRAGS; ++i) dst[i] = p[((RS == 2 || i < 4) ? i : i + 4) * 64];
     };
     auto load_x = [&](uint4 (&dst)[NX]) {
+#ifdef FV_PROBE_NO_X
+        return;
+#endif
         const bool live = rq.j < rq.n;
         const uint4* p = live ? rq.xp : zeros;
 #pragma unroll
@@ -186,6 +192,15 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     };
 
     uint4 x[3][NX], w[3][FV_FRAGS];
+    // Timing aid (stand-alone probe builds only): with FV_PROBE_NO_W / FV_PROBE_NO_X the weight / activation
+    // requests are left out and the matrix instructions run on constants, which shows what a launch costs
+    // apart from its operand traffic.  The results are meaningless; nothing in the library defines these.
+#ifdef FV_PROBE_NO_W
+    for (int i_ = 0; i_ < 3; ++i_) for (int j_ = 0; j_ < FV_FRAGS; ++j_) w[i_][j_] = make_uint4(tid, 1, 0, 0);
+#endif
+#ifdef FV_PROBE_NO_X
+    for (int i_ = 0; i_ < 3; ++i_) for (int j_ = 0; j_ < NX; ++j_) x[i_][j_] = make_uint4(tid, 0, 0, 0);
+#endif
     enter_slice(0);
     FV_TS(2)
     // prologue in the loop's own issue order: X(0) W(0) X(1) W(1) X(2) W(2)
