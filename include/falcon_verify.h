@@ -61,8 +61,13 @@ typedef enum fv_status {
     FV_E_HIP = -9,            /* a HIP runtime call failed (no usable GPU, launch error) */
     FV_E_NONFINITE = -10,     /* the logits of some node hold a NaN or an infinity: there is no greedy choice;
                                  the committed length and the pending root are left as they were */
-    FV_E_SCRATCH_LIMIT = -11  /* fv_verify_tree_noalloc: n_nodes > FV_NOALLOC_MAX_NODES, or the shape needs more
+    FV_E_SCRATCH_LIMIT = -11, /* fv_verify_tree_noalloc: n_nodes > FV_NOALLOC_MAX_NODES, or the shape needs more
                                  scratch than the library's static device array holds */
+    FV_E_EXCHANGE_TIMEOUT = -12 /* a GEMM workgroup waited about a third of a second for another workgroup's partial
+                                 sums and gave up (a device so oversubscribed that the workgroups of one launch do
+                                 not run together, or a device fault).  The step's results are invalid, every kernel
+                                 still ran to its end, and the context (or drafter) returns this from every later
+                                 step: destroy it. */
 } fv_status;
 
 enum { FV_F32 = 0, FV_BF16 = 1 };

@@ -10,7 +10,7 @@ _LIB = None
 
 STATUS = {0: "FV_OK", -1: "FV_E_BAD_ARG", -2: "FV_E_TREE_ORDER", -3: "FV_E_TREE_DEPTH", -4: "FV_E_TOKEN_RANGE",
           -5: "FV_E_TREE_TOO_BIG", -6: "FV_E_CACHE_FULL", -7: "FV_E_ROOT_MISMATCH", -8: "FV_E_NO_PREFILL",
-          -9: "FV_E_HIP", -10: "FV_E_NONFINITE", -11: "FV_E_SCRATCH_LIMIT"}
+          -9: "FV_E_HIP", -10: "FV_E_NONFINITE", -11: "FV_E_SCRATCH_LIMIT", -12: "FV_E_EXCHANGE_TIMEOUT"}
 PHASES = ("gemm", "fixup", "attn", "other")
 
 

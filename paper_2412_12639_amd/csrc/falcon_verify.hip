@@ -20,6 +20,7 @@
 #define FV_MAX_DEVICES 64
 static __device__ __align__(256) unsigned char scratch[FV_STATIC_SCRATCH_BYTES];
 static char* g_static_scratch[FV_MAX_DEVICES];
+static bool g_static_dirty[FV_MAX_DEVICES];
 static std::mutex g_static_scratch_mu;
 
 // small fill kernel (tickets that must start at zero): a memset node is not what a caller that
@@ -46,7 +47,7 @@ static __global__ __launch_bounds__(256) void k_stream_read(const uint4* p, size
 }
 
 // Device address of the current device's copy of `scratch` (looked up once per device).
-static int static_scratch_ptr(char** out) {
+static int static_scratch_ptr(char** out, bool** dirty) {
     int dev = -1;
     HIPCHK(hipGetDevice(&dev));
     if (dev < 0 || dev >= FV_MAX_DEVICES) return FV_E_BAD_ARG;
@@ -58,6 +59,7 @@ static int static_scratch_ptr(char** out) {
         g_static_scratch[dev] = (char*)ptr;
     }
     *out = g_static_scratch[dev];
+    *dirty = &g_static_dirty[dev];
     return FV_OK;
 }
 
@@ -335,6 +337,7 @@ const char* fv_status_str(int s) {
         case FV_E_NO_PREFILL: return "weights or prefill missing";
         case FV_E_HIP: return "HIP runtime error";
         case FV_E_NONFINITE: return "non-finite logits";
+        case FV_E_EXCHANGE_TIMEOUT: return "a GEMM workgroup waited in vain for another one's partial sums (the context is unusable)";
         case FV_E_SCRATCH_LIMIT: return "beyond the limits of the static scratch (more than 64 nodes, or a shape whose partial tiles exceed it)";
     }
     return "unknown status";
@@ -390,6 +393,7 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
     }
     { const char* e = getenv("FV_GEMM_FIX"); c->gemm_fix = e ? atoi(e) : 1; }
     { const char* e = getenv("FV_ATTN"); c->attn_canon = e && !strcmp(e, "invariant"); }
+    { const char* e = getenv("FV_EXCHANGE_TEST"); c->exchange_test = e && !strcmp(e, "timeout"); }
     auto fail = [&](int code) { fv_destroy(c); return code; };
     if (hipHostMalloc((void**)&c->h_in, 3 * FV_MAX_TREE * 4, hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
     if (hipHostMalloc((void**)&c->h_res, sizeof(FvResult), hipHostMallocDefault) != hipSuccess) return fail(FV_E_HIP);
@@ -421,6 +425,7 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
         a.part = c->at<float>(ly.off_part); a.part_bytes = (unsigned)ly.part_bytes;
         a.tickets = c->at<int>(ly.off_tickets); a.ticket_bytes = (size_t)ngmax * 4;
         a.apart = c->at<float>(ly.off_apart); a.atick = c->at<int>(ly.off_atick); a.atick_bytes = (size_t)cfg->n_q_heads * 8 * 4;
+        a.dirty = &c->arena_part_dirty;
         a.aslots = 32;   // the area holds 8 node blocks x 8 parts per head: 32 triples for each of a 64-row step's two blocks
         c->scr = &c->scr_arena;
         // the same buffers for steps of up to 64 rows (direct and paired GEMM forms, two 32-node attention
@@ -435,7 +440,8 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
         auto take = [&](size_t bytes) { size_t r = o; o = rup(o + bytes, 256); return r; };
         const size_t o_part = take(pb), o_tick = take(a.ticket_bytes), o_ap = take(ab), o_at = take(a.atick_bytes);
         char* base = nullptr;
-        rc = static_scratch_ptr(&base);
+        bool* static_dirty = nullptr;
+        rc = static_scratch_ptr(&base, &static_dirty);
         if (rc) return fail(rc);
         if (o <= FV_STATIC_SCRATCH_BYTES && pb < ((size_t)1 << 31)) {
             StepScratch& t = c->scr_static;
@@ -443,6 +449,7 @@ int fv_create_ex(const fv_cfg* cfg, void* dev_arena, size_t arena_bytes, void* h
             t.tickets = (int*)(base + o_tick); t.ticket_bytes = a.ticket_bytes;
             t.apart = (float*)(base + o_ap); t.atick = (int*)(base + o_at); t.atick_bytes = a.atick_bytes;
             t.aslots = 8;
+            t.dirty = static_dirty;
         }
     }
     *out = c;

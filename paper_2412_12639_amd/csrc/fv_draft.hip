@@ -136,6 +136,7 @@ int fv_drafter_create(fv_ctx* target, int32_t k, void* dev_arena, size_t arena_b
     if (d->lay.part_bytes >= ((size_t)1 << 31)) return fail(FV_E_BAD_ARG);
     d->scr.part = d->at<float>(d->lay.off_part); d->scr.part_bytes = (unsigned)d->lay.part_bytes;
     d->scr.tickets = d->at<int>(d->lay.off_tickets); d->scr.ticket_bytes = d->lay.ticket_bytes;
+    d->scr.dirty = &d->part_dirty;
     {   // kernel per LSTM matrix up to 64 rows: the same rule (and the same tuning switch) as the decoder's matrices
         const int base = gemm_kind_from_env();
         d->kind_ih0 = (base == GEMM_PAIRED && !d->lay.ih0.paired_ok) ? GEMM_DIRECT : base;
@@ -231,8 +232,9 @@ int fv_draft_commit(fv_drafter* d, const int32_t* tokens, const float* dev_featu
         hipLaunchKernelGGL(k_state_keep, dim3((2 * cf.hidden + 255) / 256), dim3(256), 0, st, ka);
         HIPCHK(hipGetLastError());
         HIPCHK(hipEventRecord(d->core->ev1, st));
-        HIPCHK(hipMemcpyAsync(d->h_out + FV_MAX_TREE, d->at<int32_t>(d->lay.off_bad), 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipMemcpyAsync(d->h_out + FV_MAX_TREE, d->at<int32_t>(d->lay.off_bad), 8, hipMemcpyDeviceToHost, st));
         HIPCHK(hipStreamSynchronize(st));
+        if (d->h_out[FV_MAX_TREE + 1]) { d->part_dirty = true; return FV_E_EXCHANGE_TIMEOUT; }
         float ms = 0.f;
         HIPCHK(hipEventElapsedTime(&ms, d->core->ev0, d->core->ev1));
         total_ms += ms;
@@ -358,8 +360,9 @@ int fv_draft_tree(fv_drafter* d, const int32_t* parent, const int32_t* depth, co
     }
     HIPCHK(hipEventRecord(d->core->ev1, st));
     HIPCHK(hipMemcpyAsync(d->h_out, d->at<int32_t>(d->lay.off_node_tok), (size_t)n * 4, hipMemcpyDeviceToHost, st));
-    HIPCHK(hipMemcpyAsync(d->h_out + FV_MAX_TREE, d->at<int32_t>(d->lay.off_bad), 4, hipMemcpyDeviceToHost, st));
+    HIPCHK(hipMemcpyAsync(d->h_out + FV_MAX_TREE, d->at<int32_t>(d->lay.off_bad), 8, hipMemcpyDeviceToHost, st));
     HIPCHK(hipStreamSynchronize(st));
+    if (d->h_out[FV_MAX_TREE + 1]) { d->part_dirty = true; return FV_E_EXCHANGE_TIMEOUT; }
     HIPCHK(hipEventElapsedTime(&d->last_ms, d->core->ev0, d->core->ev1));
     d->n_rows = next_row;
     if (d->h_out[FV_MAX_TREE]) {

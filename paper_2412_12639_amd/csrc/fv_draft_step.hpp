@@ -36,6 +36,9 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
         ga.rinv_out = c->at<float>(ly.off_rinv);
         ga.T = rows; ga.n_strips = p.n_strips;
         ga.ssq_in = c->at<float>(ly.off_ssq); ga.n_ssq = 0; ga.inv_h = 0.f; ga.eps = 1.f;
+        ga.mark = c->exchange_test ? 0u : 1u;
+        ga.spin_limit = c->exchange_test ? 2u : FV_EXCHANGE_SPINS;
+        ga.fault = d->at<uint32_t>(dl.off_bad) + 1;   // second word of the error slot
         return ga;
     };
     // a matrix of the decoder block (plans and tables of the one-layer context)
@@ -82,7 +85,7 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
             const void* X = layer == 0 ? d->at<void>(dl.off_xz) : d->at<void>(dl.off_xh);
             GemmArgs ga = plain_args(fin.pick(kind), d->arena + dl.off_w[2 * layer], X, n);
             ga.logits = d->at<float>(dl.off_gin); ga.Vpad = 4 * h;
-            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, kind);
+            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, kind, &d->scr);
             if (rc) return rc;
         }
         int l0 = ps.l0;
@@ -96,7 +99,7 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
             const int kind = kind_for(Tpl, d->kind_hh);
             GemmArgs ga = plain_args(dl.hh.pick(kind), d->arena + dl.off_w[2 * layer + 1], d->at<void>(dl.off_xprev), nl);
             ga.logits = d->at<float>(dl.off_grec); ga.Vpad = 4 * h;
-            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tpl, ga, kind);
+            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tpl, ga, kind, &d->scr);
             if (rc) return rc;
             LstmCellArgs ca;
             ca.tab = tab; ca.g_in = d->at<float>(dl.off_gin); ca.g_rec = d->at<float>(dl.off_grec);
@@ -118,7 +121,7 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
         GemmArgs ga = core_args(GM_QKV, core_kind(GM_QKV), c->layer_w(0, 0), ly.off_xb, true);
         ga.q_out = c->at<void>(ly.off_q); ga.q_lo_out = c->at<void>(ly.off_qlo); ga.kcache = c->kc(0); ga.vcache = c->vc(0);
         ga.rope_cs = c->at<float2>(ly.off_rope); ga.Hq = cf.n_q_heads; ga.Hkv = cf.n_kv_heads; ga.L = slot0; ga.S_pad = ly.S_pad;
-        int rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, core_kind(GM_QKV));
+        int rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, core_kind(GM_QKV), &d->scr);
         if (rc) return rc;
     }
     {
@@ -136,20 +139,20 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
         GemmArgs ga = core_args(GM_O, core_kind(GM_O), c->layer_w(0, 1), ly.off_attn, false);
         ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb); ga.gain_next = c->gain(1);
         ga.ssq_out = c->at<float>(ly.off_ssq);
-        int rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, core_kind(GM_O));
+        int rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, core_kind(GM_O), &d->scr);
         if (rc) return rc;
     }
     {
         GemmArgs ga = core_args(GM_GU, core_kind(GM_GU), c->layer_w(0, 2), ly.off_xb, true);
         ga.act = c->at<void>(ly.off_act);
-        int rc = launch_gemm<EL, D, EPI_SWIGLU>(c, Tp, ga, core_kind(GM_GU));
+        int rc = launch_gemm<EL, D, EPI_SWIGLU>(c, Tp, ga, core_kind(GM_GU), &d->scr);
         if (rc) return rc;
     }
     {   // down projection; the block's output is the predicted feature, which the LM head takes as it is (gain 1, no norm)
         GemmArgs ga = core_args(GM_DN, core_kind(GM_DN), c->layer_w(0, 3), ly.off_act, false);
         ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb); ga.gain_next = d->at<float>(dl.off_ones);
         ga.ssq_out = c->at<float>(ly.off_ssq);
-        int rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, core_kind(GM_DN));
+        int rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, core_kind(GM_DN), &d->scr);
         if (rc) return rc;
     }
     {
@@ -160,7 +163,7 @@ int run_draft_pass(fv_drafter* d, const DraftPass& ps) {
     {   // the target's LM head on the predicted features; the logits of every phase row are kept (row r at r * Vpad)
         GemmArgs ga = core_args(GM_LM, core_kind(GM_LM), d->target->arena + d->target->lay.off_lm, ly.off_xb, false);
         ga.logits = d->at<float>(dl.off_logits) + (size_t)ps.r0 * ly.Vpad; ga.Vpad = ly.Vpad;
-        int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, core_kind(GM_LM));
+        int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, core_kind(GM_LM), &d->scr);
         if (rc) return rc;
     }
     {

@@ -29,9 +29,10 @@
 
 
 // Shared-memory needs, in floats: one accumulator exchange area [4 wavefronts][tiles][16][64],
-// RMSNorm factors [Tp], reduction scratch [1024], ticket.
-#define FV_DIRECT_SMEM_FLOATS(TB) (4 * (TB) * 1024 + (TB) * 32 + 1024 + 4)
-#define FV_PAIRED_SMEM_FLOATS(TB) (4 * 2 * (TB) * 1024 + (TB) * 32 + 1024 + 4)
+// RMSNorm factors [Tp], reduction scratch [1024], 4 spare words, parked sums [FV_PARK][tiles][16][64].
+#define FV_PARK 3   // reduced tiles of this many segments are kept in LDS before anything is stored
+#define FV_DIRECT_SMEM_FLOATS(TB) (4 * (TB) * 1024 + (TB) * 32 + 1024 + 4 + FV_PARK * (TB) * 1024)
+#define FV_PAIRED_SMEM_FLOATS(TB) (4 * 2 * (TB) * 1024 + (TB) * 32 + 1024 + 4 + FV_PARK * 2 * (TB) * 1024)
 
 // This workgroup's range of the (row group, K stage) space and this wavefront's slices of it.
 struct DPlan {
@@ -231,102 +232,6 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         __syncthreads();
     }
 
-    // end of segment s for the whole workgroup: every wavefront has put its sums into `red`
-    auto finish_segment = [&](int s) {
-        int gi, b0, nb;
-        pl.segment(s, gi, b0, nb);
-        __syncthreads();
-        // wavefront t < NT sums tile t = (strip r of the row group, token block tb) over the four
-        // wavefronts, in wavefront order
-        const int strip = gi * RS + wave / TB, tb_ = wave % TB;
-        const float4* slot0 = (const float4*)red + lane;
-        float r[16];
-        if (wave < NT) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 sum = slot0[((size_t)(0 * NT + wave) * 4 + q) * 64];
-#pragma unroll
-                for (int w_ = 1; w_ < 4; ++w_) {
-                    const float4 v = slot0[((size_t)(w_ * NT + wave) * 4 + q) * 64];
-                    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
-                }
-                r[4 * q] = sum.x; r[4 * q + 1] = sum.y; r[4 * q + 2] = sum.z; r[4 * q + 3] = sum.w;
-            }
-        }
-        // what the residual and the rotary epilogues read besides the GEMM result is requested
-        // now, so that it travels while the partial tiles are exchanged
-        constexpr bool resid = EPI == EPI_RESID, qkv = EPI == EPI_QKV;
-        EpiPre pre;
-        const bool mine_out = wave < NT && strip < a.n_strips;
-        bool have_pre = false;
-        if (resid && mine_out) { resid_preload(a, Tp, strip, tb_, lane, pre); have_pre = true; }
-        if (qkv && mine_out) have_pre = rope_preload<D>(a, strip, tb_, lane, pre);
-        bool finish = (nb == a.NB);   // the whole K range was ours: straight to the epilogue
-        if (!finish) {
-            // partial tile out with write-through stores (partials and tickets cross XCDs whose L2s
-            // are not coherent), acknowledged before the ticket is drawn.  128-bit accesses through a
-            // raw buffer descriptor over the partial area (the agent-scope policy bit of the atomics;
-            // addresses bounds-checked in hardware), layout per tile [4 register quads][64 lanes][4]:
-            // four requests per tile, so the tiles of four contributors fit in flight at once.
-            constexpr int SC1 = 16;
-            const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
-            auto tile_ofs = [&](int wg_, int seg_) -> unsigned {
-                return ((unsigned)((wg_ * a.segmax + seg_) * NT + wave) * 1024u + (unsigned)lane * 4u) * 4u;
-            };
-            if (wave < NT) {
-                const unsigned o = tile_ofs(wg, s);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    u32x4 v;
-                    v.x = __float_as_uint(r[4 * q]); v.y = __float_as_uint(r[4 * q + 1]);
-                    v.z = __float_as_uint(r[4 * q + 2]); v.w = __float_as_uint(r[4 * q + 3]);
-                    __builtin_amdgcn_raw_buffer_store_b128(v, prs, o + q * 1024u, 0, SC1);
-                }
-            }
-            const int c_first = a.tab_cf[gi], c_last = a.tab_cl[gi];
-            // Segment index of this row group inside a contributor's partial area: the ranges are
-            // contiguous, so every contributor but the first starts inside the group (index 0); the
-            // first one's index is fetched now, not between the ticket and the partial loads.
-            const int seg_first = gi - a.tab_g0[c_first];
-            handoff_release();
-            __syncthreads();
-            if (tid == 0) *ticket_lds = __hip_atomic_fetch_add(&a.tickets[gi], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            handoff_acquire();
-            if (*ticket_lds == c_last - c_first) {
-                finish = true;
-                if (tid == 0) __hip_atomic_store(&a.tickets[gi], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-                if (wave < NT) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) r[i] = 0.f;
-                    for (int c0 = c_first; c0 <= c_last; c0 += 4) {   // ascending order, four tiles in flight
-                        u32x4 v[4][4];
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            const int c = (c0 + k <= c_last) ? c0 + k : c_last;
-                            const unsigned o = tile_ofs(c, (c == c_first) ? seg_first : 0);
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) v[k][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + q * 1024u, 0, SC1);
-                        }
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            const float m = (c0 + k <= c_last) ? 1.f : 0.f;
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) {
-                                r[4 * q] += m * __uint_as_float(v[k][q].x);
-                                r[4 * q + 1] += m * __uint_as_float(v[k][q].y);
-                                r[4 * q + 2] += m * __uint_as_float(v[k][q].z);
-                                r[4 * q + 3] += m * __uint_as_float(v[k][q].w);
-                            }
-                        }
-                    }
-                }
-            }
-        }
-        if (finish && mine_out) gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, have_pre);
-        __syncthreads();   // `red` and ticket_lds are reused
-    };
-
     // One stage: multiply what register set S holds, then request into it the stage three ahead.
 #define FV_DSTAGE(S)                                                                        \
     {                                                                                       \
@@ -341,6 +246,138 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
         __builtin_amdgcn_sched_barrier(0);                                                  \
         advance();                                                                          \
     }
+
+    // ---- what happens to the sums of a segment
+    //
+    // Nothing leaves the compute unit in the middle of a range.  A global store between the streaming
+    // requests stalls the wavefront's stream for several microseconds (measured: one 16-byte store per
+    // lane in mid-range costs a launch what 25 KiB of weights per wavefront cost), whether it is a
+    // partial tile for another workgroup or the output of a finished row group.  So at the end of a
+    // segment the four wavefronts add their accumulators through LDS and the sum is parked in LDS;
+    // every FV_PARK segments, and at the end of the range, the parked tiles are dealt with together:
+    // first the partial tiles other workgroups wait for are stored, then the row groups this
+    // workgroup finishes get their epilogue.  (Ranges of more than FV_PARK segments -- very wide
+    // matrices -- pay the mid-range stall once per FV_PARK segments.)
+    //
+    // Who finishes a row group: whoever had its whole K range, else its FIRST contributor.  The ranges
+    // are contiguous, so the first contributor meets the group in the last segment of its own range
+    // and every other contributor in its first (segment index 0 of its partial area).
+    //
+    // Partial tiles cross XCDs whose L2s are not coherent: write-through stores and loads that bypass
+    // the caches, 128 bits per lane through a raw buffer descriptor over the partial area (addresses
+    // bounds-checked in hardware), layout per tile [4 register quads][64 lanes][4].  No
+    // acknowledgement, ticket or flag: the data says itself whether it has arrived.  The partial area
+    // is all zeros whenever a launch of these kernels starts; a contributor sets the lowest mantissa
+    // bit of every value it stores, so a reader that finds that bit in all 16 values of all 64 lanes
+    // of a tile has the whole tile, whatever order the stores landed in (every 4-byte element vouches
+    // for itself).  The reader clears the bit again before it adds, so a sum does not depend on it,
+    // and writes zeros back over every tile it has consumed, which leaves the area as it found it.
+    float4* const park = (float4*)(ticket_lds + 4);          // [FV_PARK][NT][4 quads][64 lanes]
+    auto store_parked = [&](int e) {                           // this wavefront's parked tile of segment e -> partial area
+        constexpr int SC1 = 16;
+        const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
+        const float4* pk = park + ((size_t)((e % FV_PARK) * NT + wave) * 4) * 64 + lane;
+        const unsigned mark = a.mark;
+        const unsigned o = ((unsigned)(wg * a.segmax * NT + wave) * 1024u + (unsigned)lane * 4u) * 4u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 f = pk[q * 64];
+            u32x4 v;
+            v.x = (__float_as_uint(f.x) & ~1u) | mark;
+            v.y = (__float_as_uint(f.y) & ~1u) | mark;
+            v.z = (__float_as_uint(f.z) & ~1u) | mark;
+            v.w = (__float_as_uint(f.w) & ~1u) | mark;
+            __builtin_amdgcn_raw_buffer_store_b128(v, prs, o + q * 1024u, 0, SC1);
+        }
+    };
+    auto flush_parked = [&](int s0, int s1) {                  // segments s0..s1 (at most FV_PARK)
+        constexpr int SC1 = 16;
+        const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
+        auto tile_ofs = [&](int wg_) -> unsigned {
+            return ((unsigned)(wg_ * a.segmax * NT + wave) * 1024u + (unsigned)lane * 4u) * 4u;
+        };
+        if (wave >= NT) return;
+        // pass 1: what other workgroups wait for
+        for (int e = s0; e <= s1; ++e) {
+            int gi, b0, nb;
+            pl.segment(e, gi, b0, nb);
+            if (nb == a.NB || wg == a.tab_cf[gi]) continue;
+            store_parked(e);
+        }
+        // pass 2: the row groups this workgroup finishes
+        for (int e = s0; e <= s1; ++e) {
+            int gi, b0, nb;
+            pl.segment(e, gi, b0, nb);
+            const bool whole = (nb == a.NB);
+            int c_first = wg, c_last = wg;
+            if (!whole) { c_first = a.tab_cf[gi]; c_last = a.tab_cl[gi]; }
+            if (wg != c_first) continue;
+            const int strip = gi * RS + wave / TB, tb_ = wave % TB;
+            // what the residual and the rotary epilogues read besides the GEMM result is requested
+            // now, so that it travels while the partial tiles are fetched
+            constexpr bool resid = EPI == EPI_RESID, qkv = EPI == EPI_QKV;
+            EpiPre pre;
+            const bool mine_out = strip < a.n_strips;
+            bool have_pre = false;
+            if (resid && mine_out) { resid_preload(a, Tp, strip, tb_, lane, pre); have_pre = true; }
+            if (qkv && mine_out) have_pre = rope_preload<D>(a, strip, tb_, lane, pre);
+            float r[16];
+            {
+                const float4* pk = park + ((size_t)((e % FV_PARK) * NT + wave) * 4) * 64 + lane;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 f = pk[q * 64];
+                    r[4 * q] = f.x; r[4 * q + 1] = f.y; r[4 * q + 2] = f.z; r[4 * q + 3] = f.w;
+                }
+            }
+            for (int c0 = c_first + 1; c0 <= c_last; c0 += 4) {   // ascending order, four tiles in flight
+                u32x4 v[4][4];
+                for (unsigned spins = 0;; ++spins) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int c = (c0 + k <= c_last) ? c0 + k : c_last;
+                        const unsigned o = tile_ofs(c);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) v[k][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + q * 1024u, 0, SC1);
+                    }
+                    unsigned all1 = 1u;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) all1 &= v[k][q].x & v[k][q].y & v[k][q].z & v[k][q].w;
+                    if (__all((int)(all1 & 1u))) break;
+                    // Not there yet (a contributor that is still streaming).  The wait is bounded: a
+                    // contributor that never delivers leaves a mark the host turns into an error.
+                    if (spins >= a.spin_limit) {
+                        if (lane == 0) __hip_atomic_store(a.fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(16);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float m = (c0 + k <= c_last) ? 1.f : 0.f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        r[4 * q] += m * __uint_as_float(v[k][q].x & ~1u);
+                        r[4 * q + 1] += m * __uint_as_float(v[k][q].y & ~1u);
+                        r[4 * q + 2] += m * __uint_as_float(v[k][q].z & ~1u);
+                        r[4 * q + 3] += m * __uint_as_float(v[k][q].w & ~1u);
+                    }
+                }
+                // the tiles just consumed go back to zero (nobody reads them again in this launch)
+                u32x4 zero4; zero4.x = 0u; zero4.y = 0u; zero4.z = 0u; zero4.w = 0u;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (c0 + k > c_last) break;
+                    const unsigned o = tile_ofs(c0 + k);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) __builtin_amdgcn_raw_buffer_store_b128(zero4, prs, o + q * 1024u, 0, SC1);
+                }
+            }
+            if (mine_out) gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, have_pre);
+        }
+    };
 
     FV_TS(5)
     for (int s = 0; s < nseg; ++s) {
@@ -363,7 +400,25 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
             for (int q = 0; q < 4; ++q)
                 my[(t_ * 4 + q) * 64] = make_float4(acc[t_][4 * q], acc[t_][4 * q + 1], acc[t_][4 * q + 2], acc[t_][4 * q + 3]);
         if (s == 0) { FV_TS(6) }
-        finish_segment(s);
+        __syncthreads();
+        // wavefront t < NT sums tile t = (strip r of the row group, token block tb) over the four
+        // wavefronts, in wavefront order, and parks the sum (read back by the same wavefront)
+        if (wave < NT) {
+            const float4* slot0 = (const float4*)red + lane;
+            float4* pk = park + ((size_t)((s % FV_PARK) * NT + wave) * 4) * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 sum = slot0[((size_t)(0 * NT + wave) * 4 + q) * 64];
+#pragma unroll
+                for (int w_ = 1; w_ < 4; ++w_) {
+                    const float4 v = slot0[((size_t)(w_ * NT + wave) * 4 + q) * 64];
+                    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+                }
+                pk[q * 64] = sum;
+            }
+        }
+        if (s % FV_PARK == FV_PARK - 1 || s == nseg - 1) flush_parked(s - s % FV_PARK, s);
+        __syncthreads();   // `red` is reused
     }
     FV_TS(7)
 #undef FV_DSTAGE

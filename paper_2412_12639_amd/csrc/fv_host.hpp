@@ -74,14 +74,20 @@ enum StepMode { STEP_VERIFY = 0, STEP_PREFILL_MID = 1, STEP_PREFILL_LAST = 2, ST
 // their tickets, attention key-split partials and their tickets.
 struct StepScratch {
     float* part = nullptr; unsigned part_bytes = 0; int* tickets = nullptr; size_t ticket_bytes = 0;
+    bool* dirty = nullptr;   // host flag: the partial area may hold something other than zeros (see launch_gemm)
     float* apart = nullptr; int* atick = nullptr; size_t atick_bytes = 0;
     int aslots = 0;   // key-part triples per (head, 32-row block) item that apart holds for a step of up to 64 rows
 };
+
+#define FV_EXCHANGE_SPINS 200000u   // looks at a partial tile that has not arrived before a finisher gives up (~0.3 s)
+
 
 struct fv_ctx {
     fv_cfg cfg;
     Layout lay;
     StepScratch scr_arena;        // inside the caller's arena
+    bool arena_part_dirty = false;
+    bool exchange_test = false;   // FV_EXCHANGE_TEST=timeout: contributors leave their partial tiles unmarked, finishers give up after two looks
     StepScratch scr_static;       // inside the library's static device array (steps of up to 64 rows); part == nullptr: does not fit
     const StepScratch* scr = nullptr;   // the one the next step uses
     char* arena = nullptr;
@@ -152,6 +158,7 @@ struct fv_drafter {
     fv_ctx* core = nullptr;
     DraftLayout lay;
     StepScratch scr;              // partial tiles and tickets large enough for every matrix of the drafter
+    bool part_dirty = false;
     char* arena = nullptr;
     int k = 0;
     bool weights_set = false;

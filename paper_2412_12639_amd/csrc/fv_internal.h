@@ -14,6 +14,9 @@
  *       group's partial tiles inside the GEMM launch (default: a second launch reduces them, one
  *       wavefront per tile, for the QKV, O and down projections).
  *   FV_ATTN = invariant       contexts start with step-invariant rows switched on (fv_set_step_invariant(ctx, 1)).
+ *   FV_EXCHANGE_TEST = timeout   test of the bounded wait in the direct / paired GEMM kernels: contributors leave their
+ *       partial tiles unmarked and finishers give up after two looks, so every step of more than one
+ *       workgroup per row group returns FV_E_EXCHANGE_TIMEOUT (every kernel still ends normally).
  *   FV_DEBUG = 1              print the failing HIP call of an FV_E_HIP status to stderr.
  */
 #ifndef FV_INTERNAL_H

@@ -112,13 +112,26 @@ __global__ void k_embed(EmbedArgs a) {
 // workgroup order (so the result does not depend on who arrives last) and runs the epilogue.
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 
+// n 32-bit words to zero (a template so that every translation unit may hold it)
+template <int UNUSED>
+__global__ void k_zero_words(uint32_t* p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 struct GemmArgs {
     const uint4* Wt;     // tiled weights [NG*R strips][NB][FRAGS][64] x 16 B
     const uint4* X;      // vector-major [NB*16][Tp] x 16 B
     const uint4* zeros;  // 32 KiB of zeros (what the direct kernels' padded stages load)
     float* part;         // partial tiles, fp32: [G][segmax][tiles of the kernel][1024]
     unsigned part_bytes; // size of that area (the 128-bit exchange addresses it through a bounds-checked buffer descriptor)
-    int* tickets;        // [NG], zero on entry, left zero on exit
+    int* tickets;        // [NG], zero on entry, left zero on exit (shared-activation kernel; the direct kernels draw no tickets)
+    // Direct / paired kernels (fv_gemm_direct.hpp): the partial area is all zeros at the start of a launch and
+    // left all zeros; a stored partial value carries `mark` in its lowest mantissa bit (1; 0 only in the host's
+    // test of the time-out).  spin_limit: re-reads of a tile that has not arrived before the finishing
+    // workgroup gives up, stores 1 to *fault and carries on with what it has.
+    unsigned mark, spin_limit;
+    unsigned* fault;
     int NG, NB, G, segmax;
     int aligned;         // direct kernels: workgroup ranges end on row-group boundaries (no partial tiles)
     // stream-K split, precomputed on the host: range start of every workgroup (G+1 entries), its

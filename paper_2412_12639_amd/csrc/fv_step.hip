@@ -54,8 +54,21 @@ int launch_gemm_paired_t(fv_ctx* c, const GemmArgs& ga) {
     return hipGetLastError() == hipSuccess ? FV_OK : FV_E_HIP;
 }
 
+// The direct and paired kernels need the partial area all zeros when they start and leave it so; the
+// shared-activation kernel (and a step that ran into the time-out) leaves partial sums behind.  `scr` is the
+// scratch `ga.part` belongs to: its host flag says which of the two states the area is in.
 template <typename EL, int D, int EPI>
-int launch_gemm(fv_ctx* c, int Tp, const GemmArgs& ga, int kind) {
+int launch_gemm(fv_ctx* c, int Tp, const GemmArgs& ga, int kind, const StepScratch* scr) {
+    const bool marked = (kind == GEMM_DIRECT || kind == GEMM_PAIRED) && Tp <= 64;
+    if (scr && scr->dirty) {
+        if (marked && *scr->dirty) {
+            const size_t n = scr->part_bytes / 4;
+            hipLaunchKernelGGL(k_zero_words<0>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, (uint32_t*)scr->part, n);
+            if (hipGetLastError() != hipSuccess) return FV_E_HIP;
+            *scr->dirty = false;
+        }
+        if (!marked) *scr->dirty = true;
+    }
     if (kind == GEMM_DIRECT) return Tp == 32 ? launch_gemm_direct_t<EL, 1, D, EPI>(c, ga) : launch_gemm_direct_t<EL, 2, D, EPI>(c, ga);
     if (kind == GEMM_PAIRED) return Tp == 32 ? launch_gemm_paired_t<EL, 1, D, EPI>(c, ga) : launch_gemm_paired_t<EL, 2, D, EPI>(c, ga);
     switch (Tp) {
@@ -181,6 +194,9 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
         ga.fix_groups = (const int4*)(ga.tab_u0 + (((size_t)2 * p.G + 1 + 2 * p.NG + 3) & ~(size_t)3)); ga.n_fix = p.n_fix; ga.rinv_out = c->at<float>(ly.off_rinv);
         ga.T = T; ga.n_strips = p.n_strips;
         ga.ssq_in = c->at<float>(ly.off_ssq); ga.n_ssq = h / 32; ga.inv_h = 1.f / (float)h; ga.eps = cf.rms_eps;
+        ga.mark = c->exchange_test ? 0u : 1u;   // the test of the time-out leaves the partial tiles unmarked
+        ga.spin_limit = c->exchange_test ? 2u : FV_EXCHANGE_SPINS;
+        ga.fault = &c->at<FvResult>(ly.off_res)->fault;
         return ga;
     };
 
@@ -194,7 +210,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             GemmArgs ga = gemm_args(GM_QKV, c->layer_w(l, 0), ly.off_xb);
             ga.q_out = c->at<void>(ly.off_q); ga.q_lo_out = c->at<void>(ly.off_qlo); ga.kcache = c->kc(l); ga.vcache = c->vc(l);
             ga.rope_cs = c->at<float2>(ly.off_rope); ga.Hq = cf.n_q_heads; ga.Hkv = cf.n_kv_heads; ga.L = L; ga.S_pad = ly.S_pad;
-            rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, kind_of(GM_QKV));
+            rc = launch_gemm<EL, D, EPI_QKV>(c, Tp, ga, kind_of(GM_QKV), c->scr);
             if (rc) return rc;
         }
         if (canon) {
@@ -221,14 +237,14 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             GemmArgs ga = gemm_args(GM_O, c->layer_w(l, 1), ly.off_attn);
             ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb); ga.gain_next = c->gain(2 * l + 1);
             ga.ssq_out = c->at<float>(ly.off_ssq);
-            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, kind_of(GM_O));
+            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, kind_of(GM_O), c->scr);
             if (rc) return rc;
         }
         {   // gate and up projections, SwiGLU
             PhaseTimer pt(c, FV_PH_GEMM);
             GemmArgs ga = gemm_args(GM_GU, c->layer_w(l, 2), ly.off_xb);
             ga.act = c->at<void>(ly.off_act);
-            rc = launch_gemm<EL, D, EPI_SWIGLU>(c, Tp, ga, kind_of(GM_GU));
+            rc = launch_gemm<EL, D, EPI_SWIGLU>(c, Tp, ga, kind_of(GM_GU), c->scr);
             if (rc) return rc;
         }
         {   // down projection, residual add, statistics + input of the next norm
@@ -237,7 +253,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             ga.x_in = ga.x = c->at<float>(ly.off_x); ga.xb = c->at<void>(ly.off_xb);
             ga.gain_next = (l + 1 < cf.n_layers) ? c->gain(2 * (l + 1)) : c->gain(2 * cf.n_layers);
             ga.ssq_out = c->at<float>(ly.off_ssq);
-            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, kind_of(GM_DN));
+            rc = launch_gemm<EL, D, EPI_RESID>(c, Tp, ga, kind_of(GM_DN), c->scr);
             if (rc) return rc;
         }
     }
@@ -247,7 +263,7 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
             PhaseTimer pt(c, FV_PH_GEMM);
             GemmArgs ga = gemm_args(GM_LM, c->at<void>(ly.off_lm), ly.off_xb);
             ga.logits = c->at<float>(ly.off_logits); ga.Vpad = ly.Vpad;
-            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, kind_of(GM_LM));
+            int rc = launch_gemm<EL, D, EPI_LOGITS>(c, Tp, ga, kind_of(GM_LM), c->scr);
             if (rc) return rc;
         }
         PhaseTimer pt(c, FV_PH_OTHER);
@@ -288,9 +304,16 @@ int run_step(fv_ctx* c, int T, StepMode mode) {
     HIPCHK(hipEventRecord(c->ev1, st));
     if (mode == STEP_VERIFY || mode == STEP_VERIFY_SAMPLED)
         HIPCHK(hipMemcpyAsync(c->h_res, c->at<FvResult>(ly.off_res), sizeof(FvResult), hipMemcpyDeviceToHost, st));
-    else if (mode == STEP_PREFILL_LAST)
-        HIPCHK(hipMemcpyAsync(&c->h_res->next_token, c->at<int32_t>(ly.off_am) + (T - 1), 4, hipMemcpyDeviceToHost, st));
+    else {
+        if (mode == STEP_PREFILL_LAST)
+            HIPCHK(hipMemcpyAsync(&c->h_res->next_token, c->at<int32_t>(ly.off_am) + (T - 1), 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipMemcpyAsync(&c->h_res->fault, &c->at<FvResult>(ly.off_res)->fault, 4, hipMemcpyDeviceToHost, st));
+    }
     HIPCHK(hipStreamSynchronize(st));
+    if (c->h_res->fault) {
+        if (c->scr->dirty) *c->scr->dirty = true;   // unconsumed partial tiles may be left behind
+        return FV_E_EXCHANGE_TIMEOUT;
+    }
     HIPCHK(hipEventElapsedTime(&c->last_ms, c->ev0, c->ev1));
     if (c->profiling) {
         for (size_t i = 0; i + 1 < c->pev_used; i += 2) {

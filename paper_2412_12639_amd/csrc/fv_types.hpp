@@ -16,6 +16,7 @@
 // Result of the longest-accepted-path scan, written by the device and copied to the host.
 struct FvResult {
     int32_t accepted_len, next_token, best, pad;
+    uint32_t fault, pad2[3];   // fault: set by a GEMM whose partial-tile wait ran out (never cleared: the context is unusable then)
     int32_t path[FV_MAX_TREE];
     int32_t accepted_tokens[FV_MAX_TREE];
 };

@@ -608,3 +608,28 @@ def test_multi_step_decoding_with_a_synthetic_drafter_is_lossless(fvmod, name):
     assert emitted[:k] == [int(t) for t in o_seq[1:1 + k]]
     say("steps", step, "tokens", len(emitted), "mean accepted length", float(np.mean(accepted)))
     g.close()
+
+
+def test_a_partial_tile_that_never_arrives_ends_in_an_error_not_a_hang(fvmod, monkeypatch):
+    """The GEMM workgroup that finishes a shared row group waits for the other workgroups' partial
+    sums with a bounded number of looks.  FV_EXCHANGE_TEST=timeout (read when the context is created)
+    makes the condition from the host: contributors leave their tiles unmarked and
+    finishers give up after two looks.  Every kernel ends normally; the step reports
+    FV_E_EXCHANGE_TIMEOUT, and so does every later step of that context."""
+    name = "small-gqa"
+    shape, weights = SHAPES[name], weights_of(name)
+    monkeypatch.setenv("FV_EXCHANGE_TEST", "timeout")
+    g = make_gpu(fvmod, shape, weights, 160, 64)
+    monkeypatch.delenv("FV_EXCHANGE_TEST")
+    prefix = fi.gen_prefix(3, 40, shape.vocab)
+    with pytest.raises(fvmod.FvError) as e1:
+        g.prefill(prefix)
+    assert e1.value.status == -12, e1.value
+    with pytest.raises(fvmod.FvError) as e2:
+        g.prefill(prefix)
+    assert e2.value.status == -12, e2.value
+    g.close()
+    # a context created without the switch is not affected
+    g2 = make_gpu(fvmod, shape, weights, 160, 64)
+    g2.prefill(prefix)
+    g2.close()
