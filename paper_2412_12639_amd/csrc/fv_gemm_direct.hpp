@@ -28,11 +28,13 @@
 // (included from fv_kernels.hpp after GemmArgs, gemm_epilogue and zero_acc)
 
 
-// Shared-memory needs, in floats: one accumulator exchange area [4 wavefronts][tiles][16][64],
-// RMSNorm factors [Tp], reduction scratch [1024], 4 spare words, parked sums [FV_PARK][tiles][16][64].
-#define FV_PARK 3   // reduced tiles of this many segments are kept in LDS before anything is stored
-#define FV_DIRECT_SMEM_FLOATS(TB) (4 * (TB) * 1024 + (TB) * 32 + 1024 + 4 + FV_PARK * (TB) * 1024)
-#define FV_PAIRED_SMEM_FLOATS(TB) (4 * 2 * (TB) * 1024 + (TB) * 32 + 1024 + 4 + FV_PARK * 2 * (TB) * 1024)
+// Shared-memory needs, in floats: two accumulator exchange areas [3 streaming wavefronts][tiles][16][64]
+// (used alternately from segment to segment), RMSNorm factors [Tp], reduction scratch [1024], 4 spare words,
+// parked sums [FV_PARK][tiles][16][64].
+#define FV_STREAMERS 3   // wavefronts 0..2 stream; wavefront 3 adds up their sums at the ends of segments
+#define FV_PARK 3        // reduced tiles of this many segments are kept in LDS before anything is stored
+#define FV_DIRECT_SMEM_FLOATS(TB) ((2 * FV_STREAMERS + FV_PARK) * (TB) * 1024 + (TB) * 32 + 1024 + 4)
+#define FV_PAIRED_SMEM_FLOATS(TB) ((2 * FV_STREAMERS + FV_PARK) * 2 * (TB) * 1024 + (TB) * 32 + 1024 + 4)
 
 // This workgroup's range of the (row group, K stage) space and this wavefront's slices of it.
 struct DPlan {
@@ -66,12 +68,13 @@ struct DPlan {
         const int rem = u1 - gi * NB;
         nb = (rem < NB ? rem : NB) - b0;
     }
-    // this wavefront's quarter [ws, we) of segment s
+    // this wavefront's third [ws, we) of segment s
     __device__ __forceinline__ void slice(int s, int& gi, int& ws, int& we) const {
         int b0, nb;
         segment(s, gi, b0, nb);
-        ws = b0 + nb * wave / 4;
-        we = b0 + nb * (wave + 1) / 4;
+        if (wave >= FV_STREAMERS) { ws = we = b0 + nb; return; }   // the fourth wavefront streams nothing
+        ws = b0 + nb * wave / FV_STREAMERS;
+        we = b0 + nb * (wave + 1) / FV_STREAMERS;
     }
 };
 
@@ -93,10 +96,9 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     constexpr int NX = SF * TB;                  // activation tiles per stage
     constexpr int NT = RS * TB;                  // accumulator tiles per wavefront
     static_assert(RS == 1 || RS == 2, "one or two strips per wavefront");
-    float* red = smem;                           // [wave][tile][16][64]
-    float* rinv_lds = red + 4 * NT * 1024;
+    float* red = smem;                           // [2][streaming wavefront][tile][16][64]
+    float* rinv_lds = red + 2 * FV_STREAMERS * NT * 1024;
     float* red_lds = rinv_lds + Tp;              // 16-byte aligned: Tp is a multiple of 32
-    int* ticket_lds = (int*)(red_lds + 1024);
     constexpr bool with_norm = EPI != EPI_RESID;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -249,15 +251,18 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
 
     // ---- what happens to the sums of a segment
     //
-    // Nothing leaves the compute unit in the middle of a range.  A global store between the streaming
-    // requests stalls the wavefront's stream for several microseconds (measured: one 16-byte store per
-    // lane in mid-range costs a launch what 25 KiB of weights per wavefront cost), whether it is a
-    // partial tile for another workgroup or the output of a finished row group.  So at the end of a
-    // segment the four wavefronts add their accumulators through LDS and the sum is parked in LDS;
-    // every FV_PARK segments, and at the end of the range, the parked tiles are dealt with together:
-    // first the partial tiles other workgroups wait for are stored, then the row groups this
-    // workgroup finishes get their epilogue.  (Ranges of more than FV_PARK segments -- very wide
-    // matrices -- pay the mid-range stall once per FV_PARK segments.)
+    // Three wavefronts stream (they take in what the compute unit can take in: a fourth adds nothing),
+    // the fourth adds up their sums at the ends of segments while they stream on: the streamers put
+    // their accumulators into one of two LDS areas, meet the fourth wavefront at a barrier and start the
+    // next segment; the fourth adds the three sets in wavefront order and PARKS the sum in LDS.
+    // Nothing leaves the compute unit in the middle of a range: a global store (or atomic) between the
+    // streaming requests costs the launch 3-6 us whichever wavefront issues it (measured: one 16-byte
+    // store per lane in mid-range, any cache policy), whether it is a partial tile for another
+    // workgroup or the output of a finished row group.  At the end of the range all four wavefronts
+    // take one tile each: the partial tiles other workgroups wait for are stored first, then the row
+    // groups this workgroup finishes get their epilogue.  (Ranges of more than FV_PARK segments -- very
+    // wide matrices -- have the fourth wavefront do that for the parked segments in mid-range, once per
+    // FV_PARK segments.)
     //
     // Who finishes a row group: whoever had its whole K range, else its FIRST contributor.  The ranges
     // are contiguous, so the first contributor meets the group in the last segment of its own range
@@ -272,37 +277,46 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
     // of a tile has the whole tile, whatever order the stores landed in (every 4-byte element vouches
     // for itself).  The reader clears the bit again before it adds, so a sum does not depend on it,
     // and writes zeros back over every tile it has consumed, which leaves the area as it found it.
-    float4* const park = (float4*)(ticket_lds + 4);          // [FV_PARK][NT][4 quads][64 lanes]
-    auto store_parked = [&](int e) {                           // this wavefront's parked tile of segment e -> partial area
-        constexpr int SC1 = 16;
-        const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
-        const float4* pk = park + ((size_t)((e % FV_PARK) * NT + wave) * 4) * 64 + lane;
-        const unsigned mark = a.mark;
-        const unsigned o = ((unsigned)(wg * a.segmax * NT + wave) * 1024u + (unsigned)lane * 4u) * 4u;
+    float4* const park = (float4*)(red_lds + 1024 + 4);       // [FV_PARK][NT][4 quads][64 lanes]
+    auto park_tile = [&](int e, int t) {                       // sums of segment e, tile t: three sets added, parked
+        const float4* sums = (const float4*)red + (size_t)(e & 1) * FV_STREAMERS * NT * 256 + lane;
+        float4* pk = park + ((size_t)((e % FV_PARK) * NT + t) * 4) * 64 + lane;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 f = pk[q * 64];
-            u32x4 v;
-            v.x = (__float_as_uint(f.x) & ~1u) | mark;
-            v.y = (__float_as_uint(f.y) & ~1u) | mark;
-            v.z = (__float_as_uint(f.z) & ~1u) | mark;
-            v.w = (__float_as_uint(f.w) & ~1u) | mark;
-            __builtin_amdgcn_raw_buffer_store_b128(v, prs, o + q * 1024u, 0, SC1);
+            float4 sum = sums[((size_t)(0 * NT + t) * 4 + q) * 64];
+#pragma unroll
+            for (int w_ = 1; w_ < FV_STREAMERS; ++w_) {
+                const float4 v = sums[((size_t)(w_ * NT + t) * 4 + q) * 64];
+                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            }
+            pk[q * 64] = sum;
         }
     };
-    auto flush_parked = [&](int s0, int s1) {                  // segments s0..s1 (at most FV_PARK)
+    auto flush_parked = [&](int s0, int s1, int t_lo, int t_hi) {   // segments s0..s1 (at most FV_PARK), tiles [t_lo, t_hi)
         constexpr int SC1 = 16;
         const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc((void*)a.part, 0, (int)a.part_bytes, 0x00020000);
-        auto tile_ofs = [&](int wg_) -> unsigned {
-            return ((unsigned)(wg_ * a.segmax * NT + wave) * 1024u + (unsigned)lane * 4u) * 4u;
-        };
-        if (wave >= NT) return;
-        // pass 1: what other workgroups wait for
+        // pass 1: what other workgroups wait for.  A segment that starts inside its row group belongs
+        // to a later contributor; one that starts the group without covering it is the first
+        // contributor's (the table says so also for the odd cases).
         for (int e = s0; e <= s1; ++e) {
             int gi, b0, nb;
             pl.segment(e, gi, b0, nb);
-            if (nb == a.NB || wg == a.tab_cf[gi]) continue;
-            store_parked(e);
+            if (nb == a.NB || (b0 == 0 && wg == a.tab_cf[gi])) continue;
+            const unsigned mark = a.mark;
+            for (int t = t_lo; t < t_hi; ++t) {
+                const float4* pk = park + ((size_t)((e % FV_PARK) * NT + t) * 4) * 64 + lane;
+                const unsigned o = ((unsigned)(wg * a.segmax * NT + t) * 1024u + (unsigned)lane * 4u) * 4u;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 f = pk[q * 64];
+                    u32x4 v;
+                    v.x = (__float_as_uint(f.x) & ~1u) | mark;
+                    v.y = (__float_as_uint(f.y) & ~1u) | mark;
+                    v.z = (__float_as_uint(f.z) & ~1u) | mark;
+                    v.w = (__float_as_uint(f.w) & ~1u) | mark;
+                    __builtin_amdgcn_raw_buffer_store_b128(v, prs, o + q * 1024u, 0, SC1);
+                }
+            }
         }
         // pass 2: the row groups this workgroup finishes
         for (int e = s0; e <= s1; ++e) {
@@ -310,115 +324,117 @@ __device__ __forceinline__ void gemm_direct_body(const GemmArgs& a, int wg, floa
             pl.segment(e, gi, b0, nb);
             const bool whole = (nb == a.NB);
             int c_first = wg, c_last = wg;
-            if (!whole) { c_first = a.tab_cf[gi]; c_last = a.tab_cl[gi]; }
-            if (wg != c_first) continue;
-            const int strip = gi * RS + wave / TB, tb_ = wave % TB;
-            // what the residual and the rotary epilogues read besides the GEMM result is requested
-            // now, so that it travels while the partial tiles are fetched
-            constexpr bool resid = EPI == EPI_RESID, qkv = EPI == EPI_QKV;
-            EpiPre pre;
-            const bool mine_out = strip < a.n_strips;
-            bool have_pre = false;
-            if (resid && mine_out) { resid_preload(a, Tp, strip, tb_, lane, pre); have_pre = true; }
-            if (qkv && mine_out) have_pre = rope_preload<D>(a, strip, tb_, lane, pre);
-            float r[16];
-            {
-                const float4* pk = park + ((size_t)((e % FV_PARK) * NT + wave) * 4) * 64 + lane;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 f = pk[q * 64];
-                    r[4 * q] = f.x; r[4 * q + 1] = f.y; r[4 * q + 2] = f.z; r[4 * q + 3] = f.w;
-                }
+            if (!whole) {
+                if (b0 != 0) continue;
+                c_first = a.tab_cf[gi]; c_last = a.tab_cl[gi];
+                if (wg != c_first) continue;
             }
-            for (int c0 = c_first + 1; c0 <= c_last; c0 += 4) {   // ascending order, four tiles in flight
-                u32x4 v[4][4];
-                for (unsigned spins = 0;; ++spins) {
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const int c = (c0 + k <= c_last) ? c0 + k : c_last;
-                        const unsigned o = tile_ofs(c);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) v[k][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + q * 1024u, 0, SC1);
-                    }
-                    unsigned all1 = 1u;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) all1 &= v[k][q].x & v[k][q].y & v[k][q].z & v[k][q].w;
-                    if (__all((int)(all1 & 1u))) break;
-                    // Not there yet (a contributor that is still streaming).  The wait is bounded: a
-                    // contributor that never delivers leaves a mark the host turns into an error.
-                    if (spins >= a.spin_limit) {
-                        if (lane == 0) __hip_atomic_store(a.fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(16);
-                }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float m = (c0 + k <= c_last) ? 1.f : 0.f;
+            for (int t = t_lo; t < t_hi; ++t) {
+                auto tile_ofs = [&](int wg_) -> unsigned {
+                    return ((unsigned)(wg_ * a.segmax * NT + t) * 1024u + (unsigned)lane * 4u) * 4u;
+                };
+                const int strip = gi * RS + t / TB, tb_ = t % TB;
+                // what the residual and the rotary epilogues read besides the GEMM result is requested
+                // now, so that it travels while the partial tiles are fetched
+                constexpr bool resid = EPI == EPI_RESID, qkv = EPI == EPI_QKV;
+                EpiPre pre;
+                const bool mine_out = strip < a.n_strips;
+                bool have_pre = false;
+                if (resid && mine_out) { resid_preload(a, Tp, strip, tb_, lane, pre); have_pre = true; }
+                if (qkv && mine_out) have_pre = rope_preload<D>(a, strip, tb_, lane, pre);
+                float r[16];
+                {
+                    const float4* pk = park + ((size_t)((e % FV_PARK) * NT + t) * 4) * 64 + lane;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        r[4 * q] += m * __uint_as_float(v[k][q].x & ~1u);
-                        r[4 * q + 1] += m * __uint_as_float(v[k][q].y & ~1u);
-                        r[4 * q + 2] += m * __uint_as_float(v[k][q].z & ~1u);
-                        r[4 * q + 3] += m * __uint_as_float(v[k][q].w & ~1u);
+                        const float4 f = pk[q * 64];
+                        r[4 * q] = f.x; r[4 * q + 1] = f.y; r[4 * q + 2] = f.z; r[4 * q + 3] = f.w;
                     }
                 }
-                // the tiles just consumed go back to zero (nobody reads them again in this launch)
-                u32x4 zero4; zero4.x = 0u; zero4.y = 0u; zero4.z = 0u; zero4.w = 0u;
+                for (int c0 = c_first + 1; c0 <= c_last; c0 += 4) {   // ascending order, four tiles in flight
+                    u32x4 v[4][4];
+                    for (unsigned spins = 0;; ++spins) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    if (c0 + k > c_last) break;
-                    const unsigned o = tile_ofs(c0 + k);
+                        for (int k = 0; k < 4; ++k) {
+                            const int c = (c0 + k <= c_last) ? c0 + k : c_last;
+                            const unsigned o = tile_ofs(c);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) __builtin_amdgcn_raw_buffer_store_b128(zero4, prs, o + q * 1024u, 0, SC1);
+                            for (int q = 0; q < 4; ++q) v[k][q] = __builtin_amdgcn_raw_buffer_load_b128(prs, o + q * 1024u, 0, SC1);
+                        }
+                        unsigned all1 = 1u;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) all1 &= v[k][q].x & v[k][q].y & v[k][q].z & v[k][q].w;
+                        if (__all((int)(all1 & 1u))) break;
+                        // Not there yet (a contributor that is still streaming).  The wait is bounded: a
+                        // contributor that never delivers leaves a mark the host turns into an error.
+                        if (spins >= a.spin_limit) {
+                            if (lane == 0) __hip_atomic_store(a.fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(16);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float m = (c0 + k <= c_last) ? 1.f : 0.f;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            r[4 * q] += m * __uint_as_float(v[k][q].x & ~1u);
+                            r[4 * q + 1] += m * __uint_as_float(v[k][q].y & ~1u);
+                            r[4 * q + 2] += m * __uint_as_float(v[k][q].z & ~1u);
+                            r[4 * q + 3] += m * __uint_as_float(v[k][q].w & ~1u);
+                        }
+                    }
+                    // the tiles just consumed go back to zero (nobody reads them again in this launch)
+                    u32x4 zero4; zero4.x = 0u; zero4.y = 0u; zero4.z = 0u; zero4.w = 0u;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if (c0 + k > c_last) break;
+                        const unsigned o = tile_ofs(c0 + k);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) __builtin_amdgcn_raw_buffer_store_b128(zero4, prs, o + q * 1024u, 0, SC1);
+                    }
                 }
+                if (mine_out) gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, have_pre);
             }
-            if (mine_out) gemm_epilogue<EL, D, EPI>(a, Tp, strip, tb_, lane, r, rinv_lds, pre, have_pre);
         }
     };
 
     FV_TS(5)
     for (int s = 0; s < nseg; ++s) {
-        int gi, ws, we;
-        pl.slice(s, gi, ws, we);
-        const int rounds = (we - ws + 2) / 3;
-        floatx16 acc[NT];
-        zero_acc<NT>(acc);
-        for (int r = 0; r < rounds; ++r) {
-            FV_DSTAGE(0)
-            FV_DSTAGE(1)
-            FV_DSTAGE(2)
-        }
-        // this wavefront's sums of segment s (zeros if none of its stages were ours) into LDS
-        // (16 bytes per lane and access: [wavefront][tile][register quad][lane])
-        float4* my = (float4*)red + (size_t)wave * NT * 256 + lane;
-#pragma unroll
-        for (int t_ = 0; t_ < NT; ++t_)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                my[(t_ * 4 + q) * 64] = make_float4(acc[t_][4 * q], acc[t_][4 * q + 1], acc[t_][4 * q + 2], acc[t_][4 * q + 3]);
-        if (s == 0) { FV_TS(6) }
-        __syncthreads();
-        // wavefront t < NT sums tile t = (strip r of the row group, token block tb) over the four
-        // wavefronts, in wavefront order, and parks the sum (read back by the same wavefront)
-        if (wave < NT) {
-            const float4* slot0 = (const float4*)red + lane;
-            float4* pk = park + ((size_t)((s % FV_PARK) * NT + wave) * 4) * 64 + lane;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 sum = slot0[((size_t)(0 * NT + wave) * 4 + q) * 64];
-#pragma unroll
-                for (int w_ = 1; w_ < 4; ++w_) {
-                    const float4 v = slot0[((size_t)(w_ * NT + wave) * 4 + q) * 64];
-                    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
-                }
-                pk[q * 64] = sum;
+        if (wave < FV_STREAMERS) {
+            int gi, ws, we;
+            pl.slice(s, gi, ws, we);
+            const int rounds = (we - ws + 2) / 3;
+            floatx16 acc[NT];
+            zero_acc<NT>(acc);
+            for (int r = 0; r < rounds; ++r) {
+                FV_DSTAGE(0)
+                FV_DSTAGE(1)
+                FV_DSTAGE(2)
             }
+            // this wavefront's sums of segment s (zeros if none of its stages were ours) into LDS
+            // (16 bytes per lane and access: [area][wavefront][tile][register quad][lane])
+            float4* my = (float4*)red + ((size_t)(s & 1) * FV_STREAMERS + wave) * NT * 256 + lane;
+#pragma unroll
+            for (int t_ = 0; t_ < NT; ++t_)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    my[(t_ * 4 + q) * 64] = make_float4(acc[t_][4 * q], acc[t_][4 * q + 1], acc[t_][4 * q + 2], acc[t_][4 * q + 3]);
+            if (s == 0) { FV_TS(6) }
         }
-        if (s % FV_PARK == FV_PARK - 1 || s == nseg - 1) flush_parked(s - s % FV_PARK, s);
-        __syncthreads();   // `red` is reused
+        // The streamers arrive here with their sums in area s & 1; the fourth wavefront arrives when it
+        // has parked segment s - 1, so area s & 1 (last read for segment s - 2) is free again, and what
+        // it parked is visible to everybody behind this barrier.
+        __syncthreads();
+        const int s0 = s - s % FV_PARK;
+        if (s == nseg - 1) {               // nothing left to stream: one tile each
+            if (wave < NT) { park_tile(s, wave); flush_parked(s0, s, wave, wave + 1); }
+        } else if (wave == FV_STREAMERS) {
+            for (int t = 0; t < NT; ++t) park_tile(s, t);
+            if (s % FV_PARK == FV_PARK - 1) flush_parked(s0, s, 0, NT);
+        }
     }
     FV_TS(7)
 #undef FV_DSTAGE
