@@ -52,7 +52,10 @@ def build_probe(verbose: bool = False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     src = os.path.join(HERE, "probe", "fv_gemm_probe.hip")
     variants = [("", []), ("_stamps", ["-DFV_PROBE_STAMPS"]), ("_no_x", ["-DFV_PROBE_NO_X"]), ("_no_w", ["-DFV_PROBE_NO_W"]),
-                ("_no_loads", ["-DFV_PROBE_NO_X", "-DFV_PROBE_NO_W"]), ("_no_loads_stamps", ["-DFV_PROBE_NO_X", "-DFV_PROBE_NO_W", "-DFV_PROBE_STAMPS"])]
+                ("_no_loads", ["-DFV_PROBE_NO_X", "-DFV_PROBE_NO_W"]), ("_no_loads_stamps", ["-DFV_PROBE_NO_X", "-DFV_PROBE_NO_W", "-DFV_PROBE_STAMPS"]),
+                # the same for a 32-token step (one block of tokens instead of two)
+                ("_t32", ["-DFV_PROBE_TB=1"]), ("_t32_no_x", ["-DFV_PROBE_TB=1", "-DFV_PROBE_NO_X"]),
+                ("_t32_no_loads", ["-DFV_PROBE_TB=1", "-DFV_PROBE_NO_X", "-DFV_PROBE_NO_W"])]
     outs = [(os.path.join(HERE, "probe", "fv_gemm_probe" + suffix), defs) for suffix, defs in variants]
     flags = [f for f in FLAGS if f != "-fPIC"]
     with ThreadPoolExecutor(min(len(outs), os.cpu_count() or 1)) as ex:

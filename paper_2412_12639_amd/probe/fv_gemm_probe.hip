@@ -1,4 +1,4 @@
-// Stand-alone timing of the library's own weight-streaming GEMM kernel (k_gemm_paired, 64 tokens) on the
+// Stand-alone timing of the library's own weight-streaming GEMM kernel (k_gemm_paired, 64 tokens, or 32 with -DFV_PROBE_TB=1) on the
 // projection shapes of a decoder layer, outside the library's step: what a launch costs when nothing
 // runs (empty kernel), what the same bytes cost as a pure streaming read, what the GEMM costs per
 // matrix and per layer, and -- in the build with -DFV_PROBE_STAMPS -- where inside a launch the time
@@ -88,8 +88,11 @@ __global__ __launch_bounds__(256, 1) void k_reread(const uint4* p, size_t n16, i
     if (acc.x == 0x12345678u) sink[threadIdx.x] = acc;
 }
 
+#ifndef FV_PROBE_TB
+#define FV_PROBE_TB 2   // 32-token blocks per step: 2 = 64 tokens (the benchmark's tree), 1 = 32 tokens
+#endif
 template <int EPI> static void launch(const GemmArgs& ga) {
-    hipLaunchKernelGGL((k_gemm_paired<BF16, 2, 128, EPI>), dim3(ga.G), dim3(256), FV_PAIRED_SMEM_FLOATS(2) * 4, 0, ga);
+    hipLaunchKernelGGL((k_gemm_paired<BF16, FV_PROBE_TB, 128, EPI>), dim3(ga.G), dim3(256), FV_PAIRED_SMEM_FLOATS(FV_PROBE_TB) * 4, 0, ga);
 }
 static void launch_epi(int epi, const GemmArgs& ga) {
     switch (epi) {
@@ -103,7 +106,7 @@ static void launch_epi(int epi, const GemmArgs& ga) {
 int main(int argc, char** argv) {
     const int h = argc > 6 ? atoi(argv[1]) : 4096, F = argc > 6 ? atoi(argv[2]) : 11008, Hq = argc > 6 ? atoi(argv[3]) : 32,
               Hkv = argc > 6 ? atoi(argv[4]) : 32, D = argc > 6 ? atoi(argv[5]) : 128, V = argc > 6 ? atoi(argv[6]) : 32000;
-    const int T = 64, Tp = 64, nwg = 256, S_pad = 1024;
+    const int T = 32 * FV_PROBE_TB, Tp = 32 * FV_PROBE_TB, nwg = 256, S_pad = 1024;
     if (D != 128 || h % 128 || F % 64 || Hq % Hkv || h != Hq * D) { printf("unsupported shape\n"); return 2; }
     const size_t wbytes = (size_t)3 << 30;
     char* W; CK(hipMalloc(&W, wbytes)); CK(hipMemset(W, 0, wbytes));
@@ -129,9 +132,9 @@ int main(int argc, char** argv) {
     };
     for (auto& c : cases)
         if ((size_t)c.p.G * c.p.segmax * 4 * 4096 > ((size_t)64 << 20) || c.p.NG > 8192) { printf("shape too large for the probe's buffers\n"); return 2; }
-    const void* fns[4] = {(const void*)k_gemm_paired<BF16, 2, 128, EPI_QKV>, (const void*)k_gemm_paired<BF16, 2, 128, EPI_RESID>,
-                          (const void*)k_gemm_paired<BF16, 2, 128, EPI_SWIGLU>, (const void*)k_gemm_paired<BF16, 2, 128, EPI_LOGITS>};
-    for (const void* f : fns) CK(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PAIRED_SMEM_FLOATS(2) * 4));
+    const void* fns[4] = {(const void*)k_gemm_paired<BF16, FV_PROBE_TB, 128, EPI_QKV>, (const void*)k_gemm_paired<BF16, FV_PROBE_TB, 128, EPI_RESID>,
+                          (const void*)k_gemm_paired<BF16, FV_PROBE_TB, 128, EPI_SWIGLU>, (const void*)k_gemm_paired<BF16, FV_PROBE_TB, 128, EPI_LOGITS>};
+    for (const void* f : fns) CK(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, FV_PAIRED_SMEM_FLOATS(FV_PROBE_TB) * 4));
     hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
 #ifdef FV_PROBE_STAMPS
     long long* dts; CK(hipMalloc(&dts, 1024 * 16 * 8)); CK(hipMemcpyToSymbol(HIP_SYMBOL(g_ts), &dts, sizeof(dts)));
@@ -153,13 +156,13 @@ int main(int argc, char** argv) {
         return ga;
     };
     float ms;
-    printf("shape: hidden %d, FFN %d, heads %d/%d x %d, vocabulary %d; 64 tokens; %d workgroups of 256 threads\n", h, F, Hq, Hkv, D, V, nwg);
+    printf("shape: hidden %d, FFN %d, heads %d/%d x %d, vocabulary %d; %d tokens; %d workgroups of 256 threads\n", h, F, Hq, Hkv, D, V, Tp, nwg);
 
     {   // launch floor
         GemmArgs ga = args_of(cases[0]);
-        for (int rep = 0; rep < 3; ++rep) hipLaunchKernelGGL(k_empty, dim3(256), dim3(256), FV_PAIRED_SMEM_FLOATS(2) * 4, 0, ga);
+        for (int rep = 0; rep < 3; ++rep) hipLaunchKernelGGL(k_empty, dim3(256), dim3(256), FV_PAIRED_SMEM_FLOATS(FV_PROBE_TB) * 4, 0, ga);
         CK(hipEventRecord(e0));
-        for (int rep = 0; rep < 100; ++rep) hipLaunchKernelGGL(k_empty, dim3(256), dim3(256), FV_PAIRED_SMEM_FLOATS(2) * 4, 0, ga);
+        for (int rep = 0; rep < 100; ++rep) hipLaunchKernelGGL(k_empty, dim3(256), dim3(256), FV_PAIRED_SMEM_FLOATS(FV_PROBE_TB) * 4, 0, ga);
         CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
         printf("[floor] empty kernel of the same launch shape, back to back: %.2f us per launch\n", ms * 10);
     }
