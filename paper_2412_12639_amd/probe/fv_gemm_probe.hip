@@ -91,8 +91,9 @@ __global__ __launch_bounds__(256, 1) void k_reread(const uint4* p, size_t n16, i
 #ifndef FV_PROBE_TB
 #define FV_PROBE_TB 2   // 32-token blocks per step: 2 = 64 tokens (the benchmark's tree), 1 = 32 tokens
 #endif
+static hipStream_t g_stream = nullptr;   // the null stream, except for the graph comparison at the end
 template <int EPI> static void launch(const GemmArgs& ga) {
-    hipLaunchKernelGGL((k_gemm_paired<BF16, FV_PROBE_TB, 128, EPI>), dim3(ga.G), dim3(256), FV_PAIRED_SMEM_FLOATS(FV_PROBE_TB) * 4, 0, ga);
+    hipLaunchKernelGGL((k_gemm_paired<BF16, FV_PROBE_TB, 128, EPI>), dim3(ga.G), dim3(256), FV_PAIRED_SMEM_FLOATS(FV_PROBE_TB) * 4, g_stream, ga);
 }
 static void launch_epi(int epi, const GemmArgs& ga) {
     switch (epi) {
@@ -239,6 +240,27 @@ int main(int argc, char** argv) {
         CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
         const double lb = (double)(cases[0].bytes + cases[1].bytes + cases[2].bytes + cases[3].bytes);
         printf("[layer] 32 x (QKV, O, gate/up, down): %.3f ms  %.1f us per layer  %.0f GB/s\n", ms, ms * 1e3 / 32, lb * 32 / ms / 1e6);
+    }
+    {   // the same 128 launches as one captured graph, replayed (does the launch path between kernels cost anything?)
+        hipStream_t cs; CK(hipStreamCreate(&cs));
+        g_stream = cs;
+        hipGraph_t graph; hipGraphExec_t exec;
+        CK(hipStreamBeginCapture(cs, hipStreamCaptureModeGlobal));
+        for (int l = 0; l < 32; ++l) for (int i = 0; i < 4; ++i) launch_epi(cases[i].epi, args_of(cases[i]));
+        CK(hipStreamEndCapture(cs, &graph));
+        CK(hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+        for (int rep = 0; rep < 3; ++rep) {
+            CK(hipEventRecord(e0, cs));
+            for (int l = 0; l < 32; ++l) for (int i = 0; i < 4; ++i) launch_epi(cases[i].epi, args_of(cases[i]));
+            CK(hipEventRecord(e1, cs)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+            printf("[graph] 128 launches on a stream : %.3f ms  %.1f us per layer\n", ms, ms * 1e3 / 32);
+            CK(hipEventRecord(e0, cs));
+            CK(hipGraphLaunch(exec, cs));
+            CK(hipEventRecord(e1, cs)); CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1));
+            printf("[graph] the same as a graph      : %.3f ms  %.1f us per layer\n", ms, ms * 1e3 / 32);
+        }
+        g_stream = nullptr;
+        CK(hipGraphExecDestroy(exec)); CK(hipGraphDestroy(graph)); CK(hipStreamDestroy(cs));
     }
     unsigned hf = 0; CK(hipMemcpy(&hf, fault, 4, hipMemcpyDeviceToHost));
     if (hf) printf("a partial tile did not arrive in time\n");
