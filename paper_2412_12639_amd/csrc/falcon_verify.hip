@@ -249,7 +249,10 @@ int run_step_d(fv_ctx* c, int T, StepMode mode) {
     return c->cfg.head_dim == 128 ? run_step<EL, 128>(c, T, mode) : run_step<EL, 64>(c, T, mode);
 }
 int run_step_any(fv_ctx* c, int T, StepMode mode) {
-    return c->cfg.dtype == FV_BF16 ? run_step_d<BF16>(c, T, mode) : run_step_d<F32>(c, T, mode);
+    const int rc = c->cfg.dtype == FV_BF16 ? run_step_d<BF16>(c, T, mode) : run_step_d<F32>(c, T, mode);
+    // a step that did not run to its end may leave partial tiles nobody consumed: have the area cleared before its next use
+    if (rc != FV_OK && c->scr && c->scr->dirty) *c->scr->dirty = true;
+    return rc;
 }
 
 template <typename EL>

@@ -65,8 +65,11 @@ void make_draft_layout(const fv_cfg& t, int n_wg, DraftLayout& L) {
 
 int pass_any(fv_drafter* d, const DraftPass& ps) {
     const fv_cfg& cf = d->core->cfg;
-    if (cf.dtype == FV_BF16) return cf.head_dim == 128 ? run_draft_pass<BF16, 128>(d, ps) : run_draft_pass<BF16, 64>(d, ps);
-    return cf.head_dim == 128 ? run_draft_pass<F32, 128>(d, ps) : run_draft_pass<F32, 64>(d, ps);
+    int rc;
+    if (cf.dtype == FV_BF16) rc = cf.head_dim == 128 ? run_draft_pass<BF16, 128>(d, ps) : run_draft_pass<BF16, 64>(d, ps);
+    else rc = cf.head_dim == 128 ? run_draft_pass<F32, 128>(d, ps) : run_draft_pass<F32, 64>(d, ps);
+    if (rc != FV_OK) d->part_dirty = true;   // a pass that stopped half-way may leave partial tiles nobody consumed
+    return rc;
 }
 
 DraftTables dev_tables(const fv_drafter* d) {
