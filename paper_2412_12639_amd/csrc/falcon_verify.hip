@@ -129,7 +129,7 @@ void plan_gemm_forms(GemmPlan& gm, GemmPlan& gd, GemmPlan& gp, bool& paired_ok, 
     plan_gemm(gm, n_strips, K, E, n_wg);
     plan_gemm(gd, gm.n_strips, gm.K, E, n_wg, 1);
     plan_gemm(gp, gm.n_strips, gm.K, E, n_wg, 2, FV_FRAGS / 2);
-    // a full K range must give each of the four wavefronts at least three stages, so that no
+    // a full K range must give each streaming wavefront at least three stages, so that no
     // wavefront meets more than two segment ends within one round of three stages
     paired_ok = gp.NB >= 12;
     // Whole row groups per workgroup need no partial-tile exchange at all, but the group counts

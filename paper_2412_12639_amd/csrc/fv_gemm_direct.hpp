@@ -1,16 +1,20 @@
 // Skinny GEMM for up to 64 tokens, "direct" form: one 32-row strip (RS = 1) or a pair of strips
-// (RS = 2, a 64-row group) per workgroup at a time, the four wavefronts split the K range of that
+// (RS = 2, a 64-row group) per workgroup at a time, three wavefronts split the K range of that
 // row group between them, and both MFMA operands go straight from global memory to registers
 // (weights from HBM, activations from L2): no LDS and no workgroup barrier inside the streaming
-// loop, so every wavefront runs its own software pipeline.
+// loop, so every streaming wavefront runs its own software pipeline.  The fourth wavefront streams
+// nothing; it adds up the others' sums where a segment ends.
 //
 // Work split: the (row group, K stage) space is cut into G contiguous ranges, one per workgroup
 // (equal stream-K ranges, or whole row groups when the host says `aligned`).  The part of a range
-// inside one row group is a segment; a wavefront's quarter of a segment is a slice.  At the end of
-// a segment the four wavefronts add their accumulators through LDS (fixed order).  A segment that
-// covers the whole K range goes to the epilogue at once.  Otherwise the workgroup stores its
-// partial tiles, draws a ticket on the row group's counter, and whoever draws the last ticket
-// sums the partial tiles in ascending workgroup order and runs the epilogue.
+// inside one row group is a segment; a streaming wavefront's third of a segment is a slice.  At the
+// end of a segment the streaming wavefronts put their accumulators into LDS, where they are added
+// in wavefront order and the sum is parked.  Nothing leaves the compute unit before the range ends.
+// Then a segment that covers the whole K range goes to the epilogue; of a row group shared by
+// several workgroups, every contributor but the first stores its partial tiles with a mark in the
+// lowest mantissa bit of every value, and the first contributor waits (a bounded number of looks)
+// until all of them are marked, adds them in ascending workgroup order, writes zeros back and runs
+// the epilogue.  The partial area is all zeros when a launch starts and when it ends.
 //
 // A stage is 8 weight tiles of 1 KiB: RS = 1: 8 fragments of one strip (a K batch) with 8*TB
 // activation tiles; RS = 2: 4 fragments of each of two strips (half a K batch) with 4*TB
